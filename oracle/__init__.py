@@ -1,0 +1,184 @@
+"""ctypes front end of the CPU oracle (``hippo_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
+import this package.  It never touches the HIP library and the HIP binding never touches it.
+
+The wrapper does argument marshalling only, plus the two input re-arrangements the boundary
+defines (the "embedding = visual keys concatenated over KV heads" default, and slicing the
+visual span out of a cache); all arithmetic is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hippo_oracle.c")
+_LIB = os.path.join(_HERE, "libhippo_oracle.so")
+
+FLAG_ATTN, FLAG_TEMP, FLAG_SPA = 1, 2, 4
+FLAG_ALL = 7
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (float64, OpenMP over independent items)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+                               "-fno-fast-math", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+_I, _I64, _VP, _D, _U = C.c_int, C.c_int64, C.c_void_p, C.c_double, C.c_uint
+_SIGS = {
+    "hippo_oracle_s_attn": [_VP, _I, _I, _I, _I, _I, _VP, _I64, _I64, _I, _VP],
+    "hippo_oracle_s_temp": [_VP, _I, _I, _I, _I, _I64, _I64, _VP],
+    "hippo_oracle_s_spa": [_VP, _I, _I, _I, _I, _I, _I, _I, _I64, _I64, _VP],
+    "hippo_oracle_fuse": [_VP, _VP, _VP, _U, _I, _I, _I, _VP],
+    "hippo_oracle_topk": [_VP, _I, _I, _I, _VP],
+    "hippo_oracle_gather": [_VP, _I, _I, _I, _I, _I, _I, _VP, _I, _VP],
+    "hippo_oracle_attention": [_VP, _I, _I, _I, _I, _I, _VP, _VP, _I64, _I64, _I, _D, _VP, _VP],
+}
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        for name, sig in _SIGS.items():
+            fn = getattr(lib, name)
+            fn.argtypes = sig
+            fn.restype = None
+        lib.hippo_oracle_threads.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _i(x) -> int:
+    return int(x)
+
+
+def threads() -> int:
+    return int(_L().hippo_oracle_threads())
+
+
+def s_attn(q_txt: np.ndarray, k_cache: np.ndarray, vis_off: int, n_vis: int) -> np.ndarray:
+    """Eq. 2.  q_txt [B,L,H,d], k_cache [B,Hkv,N,d] -> [B,N_v] float64."""
+    q_txt, k_cache = _f32(q_txt), _f32(k_cache)
+    B, L, H, d = q_txt.shape
+    _, Hkv, N, _ = k_cache.shape
+    k_vis = np.ascontiguousarray(k_cache[:, :, vis_off:vis_off + n_vis, :])
+    out = np.zeros((B, n_vis), dtype=np.float64)
+    _L().hippo_oracle_s_attn(_p(q_txt), B, L, H, Hkv, d, _p(k_vis),
+                             C.c_int64(Hkv * n_vis * d), C.c_int64(n_vis * d), n_vis, _p(out))
+    return out
+
+
+def keys_as_embedding(k_cache: np.ndarray, vis_off: int, n_vis: int) -> np.ndarray:
+    """The boundary's default embedding: token j's vector is its keys of all KV heads,
+    concatenated in head order.  [B,Hkv,N,d] -> [B,N_v,Hkv*d]."""
+    k_cache = _f32(k_cache)
+    B, Hkv, N, d = k_cache.shape
+    kv = k_cache[:, :, vis_off:vis_off + n_vis, :]
+    return np.ascontiguousarray(kv.transpose(0, 2, 1, 3)).reshape(B, n_vis, Hkv * d)
+
+
+def s_temp(emb: np.ndarray, n_frames: int) -> np.ndarray:
+    """Eq. 3-4.  emb [B,N_v,de] -> [B,N_v] float64."""
+    emb = _f32(emb)
+    B, Nv, de = emb.shape
+    P = Nv // n_frames
+    out = np.zeros((B, Nv), dtype=np.float64)
+    _L().hippo_oracle_s_temp(_p(emb), B, n_frames, P, de, C.c_int64(Nv * de), C.c_int64(de), _p(out))
+    return out
+
+
+def s_spa(emb: np.ndarray, n_frames: int, grid_h: int, grid_w: int, crop_h: int = 5,
+          crop_w: int = 5) -> np.ndarray:
+    """Eq. 5-6.  emb [B,N_v,de] -> [B,N_v] float64."""
+    emb = _f32(emb)
+    B, Nv, de = emb.shape
+    assert Nv == n_frames * grid_h * grid_w
+    out = np.zeros((B, Nv), dtype=np.float64)
+    _L().hippo_oracle_s_spa(_p(emb), B, _i(n_frames), _i(grid_h), _i(grid_w), _i(crop_h), _i(crop_w), de,
+                            C.c_int64(Nv * de), C.c_int64(de), _p(out))
+    return out
+
+
+def fuse(sa: np.ndarray, st: np.ndarray, ss: np.ndarray, n_frames: int,
+         flags: int = FLAG_ALL) -> np.ndarray:
+    """Eq. 7.  three [B,N_v] float64 -> [B,N_v] float64."""
+    sa = np.ascontiguousarray(sa, dtype=np.float64)
+    st = np.ascontiguousarray(st, dtype=np.float64)
+    ss = np.ascontiguousarray(ss, dtype=np.float64)
+    B, Nv = sa.shape
+    out = np.zeros((B, Nv), dtype=np.float64)
+    _L().hippo_oracle_fuse(_p(sa), _p(st), _p(ss), C.c_uint(flags), B, n_frames, Nv // n_frames, _p(out))
+    return out
+
+
+def score_tokens(q_txt, k_cache, vis_off, n_frames, grid_h, grid_w, crop_h=5, crop_w=5,
+                 emb: Optional[np.ndarray] = None, flags: int = FLAG_ALL
+                 ) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 2-7 end to end.  Returns (scores [B,N_v], components [3,B,N_v]) in float64."""
+    n_vis = n_frames * grid_h * grid_w
+    if emb is None:
+        emb = keys_as_embedding(k_cache, vis_off, n_vis)
+    sa = s_attn(q_txt, k_cache, vis_off, n_vis)
+    st = s_temp(emb, n_frames)
+    ss = s_spa(emb, n_frames, grid_h, grid_w, crop_h, crop_w)
+    return fuse(sa, st, ss, n_frames, flags), np.stack([sa, st, ss])
+
+
+def topk(scores: np.ndarray, k: int) -> np.ndarray:
+    """Top-k of fp32 scores, ties to the lower index, output ascending.  [B,N] -> [B,k] int32."""
+    scores = _f32(scores)
+    B, N = scores.shape
+    idx = np.full((B, k), -1, dtype=np.int32)
+    _L().hippo_oracle_topk(_p(scores), B, N, k, _p(idx))
+    return idx
+
+
+def gather(src: np.ndarray, vis_off: int, n_vis: int, idx: np.ndarray) -> np.ndarray:
+    """[B,Hkv,N,d] -> [B,Hkv,N-N_v+k,d] (prefix | kept visual rows | rest), bit copy."""
+    src = _f32(src)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    B, Hkv, N, d = src.shape
+    k = idx.shape[1]
+    dst = np.empty((B, Hkv, N - n_vis + k, d), dtype=np.float32)
+    _L().hippo_oracle_gather(_p(src), B, Hkv, N, d, vis_off, n_vis, _p(idx), k, _p(dst))
+    return dst
+
+
+def attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, ctx_len: int,
+              scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """q [B,q_len,H,d]; caches [B,Hkv,>=ctx_len+q_len,d].  Row i sees entries [0, ctx_len+i].
+    Returns (out [B,q_len,H,d], lse [B,H,q_len]) in float64."""
+    q, k_cache, v_cache = _f32(q), _f32(k_cache), _f32(v_cache)
+    B, q_len, H, d = q.shape
+    _, Hkv, N, _ = k_cache.shape
+    assert N >= ctx_len + q_len and v_cache.shape == k_cache.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((B, q_len, H, d), dtype=np.float64)
+    lse = np.zeros((B, H, q_len), dtype=np.float64)
+    _L().hippo_oracle_attention(_p(q), B, q_len, H, Hkv, d, _p(k_cache), _p(v_cache),
+                                C.c_int64(Hkv * N * d), C.c_int64(N * d), ctx_len,
+                                C.c_double(scale), _p(out), _p(lse))
+    return out, lse
