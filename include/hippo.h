@@ -1,0 +1,184 @@
+/*
+ * hippo.h -- C ABI of the MI355X (gfx950) implementation of HIPPO's data-parallel hot path:
+ * semantic-aware visual-token scoring and selection, construction of the pruned draft KV cache,
+ * and the two attention calls that video parallel speculative decoding overlaps (draft decode over
+ * the pruned cache, target verification of gamma+1 tokens over the full cache).
+ *
+ * Conventions common to every entry point
+ *  - All data pointers are DEVICE pointers owned and allocated by the caller.  The library never
+ *    allocates or frees device memory and never synchronises: it validates its arguments on the
+ *    host, enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *    and returns.  Outputs are valid once the caller has synchronised that stream.  Calls on
+ *    different streams may run concurrently as long as their outputs and workspaces are distinct.
+ *  - The descriptor structs are HOST pointers, read before the call returns.
+ *  - Every call returns a status (HIPPO_OK = 0).  Validation happens before any kernel is
+ *    launched: on a non-zero status nothing has been enqueued and no output was touched.  No
+ *    exception crosses the boundary.
+ *  - `workspace` is device scratch of at least hippo_workspace_bytes(...) bytes, 256-byte aligned,
+ *    private to the call until the stream has passed it.
+ *  - Data pointers must be 16-byte aligned; strides are in elements and must keep every row
+ *    16-byte aligned (multiples of 8 for bf16, of 4 for fp32).  head_dim is 64 or 128.
+ *  - dtype: HIPPO_DTYPE_F32 or HIPPO_DTYPE_BF16 for q / K / V / emb / attention outputs.  Scores,
+ *    attention mass and log-sum-exp are always fp32, indices int32.  Accumulation is fp32;
+ *    bf16 outputs are rounded to nearest even.
+ */
+#ifndef HIPPO_H_
+#define HIPPO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum hippo_status {
+  HIPPO_OK = 0,
+  HIPPO_ERR_NULL_ARG = 1,            /* a required pointer is NULL */
+  HIPPO_ERR_BAD_SHAPE = 2,           /* a size, count, stride or index range is invalid */
+  HIPPO_ERR_BAD_DTYPE = 3,           /* dtype is not one of the two supported */
+  HIPPO_ERR_BAD_ALIGN = 4,           /* a pointer or stride breaks the 16-byte rule */
+  HIPPO_ERR_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes below hippo_workspace_bytes(...) */
+  HIPPO_ERR_HIP = 6                  /* a HIP runtime call (launch) failed */
+};
+
+enum hippo_dtype { HIPPO_DTYPE_F32 = 0, HIPPO_DTYPE_BF16 = 1 };
+
+enum hippo_call {
+  HIPPO_CALL_SCORE_TOKENS = 0,
+  HIPPO_CALL_SELECT_GATHER_KV = 1,
+  HIPPO_CALL_DRAFT_ATTENTION = 2,
+  HIPPO_CALL_VERIFY_ATTENTION = 3
+};
+
+/* which terms of the holistic score are enabled (the paper's ablation removes one at a time) */
+enum hippo_score_flags {
+  HIPPO_SCORE_ATTN = 1u,            /* global semantic relevance, Eq. 2 */
+  HIPPO_SCORE_TEMP = 2u,            /* inter-frame temporal redundancy, Eq. 3-4 */
+  HIPPO_SCORE_SPA = 4u,             /* intra-frame spatial redundancy, Eq. 5-6 */
+  HIPPO_SCORE_ALL = 7u,
+  HIPPO_SCORE_ACCUMULATE_ONLY = 8u  /* add this layer's attention mass into attn_mass_inout and stop
+                                       (the outer layer sum of Eq. 2); no other output is written */
+};
+
+/* A K or V cache (or the q/out heads that go with it).
+ * Element (b, hk, n, c) of a cache lives at base + b*stride_b + hk*stride_h + n*stride_n + c. */
+typedef struct hippo_kv_desc {
+  int32_t batch;
+  int32_t n_q_heads;   /* H; multiple of n_kv_heads.  Query head h reads KV head h / (H / H_kv) */
+  int32_t n_kv_heads;  /* H_kv */
+  int32_t head_dim;    /* d_k: 64 or 128 */
+  int32_t dtype;       /* enum hippo_dtype */
+  int64_t stride_b, stride_h, stride_n;  /* elements; stride_n >= head_dim */
+} hippo_kv_desc;
+
+/* Where the video sits inside the sequence and how its tokens are arranged.
+ * Visual token j = f*grid_h*grid_w + y*grid_w + x is cache row vis_offset + j.
+ * Crops (Eq. 5-6) are non-overlapping crop_h x crop_w tiles of each frame anchored at (0,0);
+ * tiles cut by the right / bottom edge keep the tokens they have. */
+typedef struct hippo_video_desc {
+  int32_t n_frames, grid_h, grid_w;
+  int32_t vis_offset;
+  int32_t crop_h, crop_w;           /* the paper uses 5 x 5; crop_h*crop_w <= 64 */
+} hippo_video_desc;
+
+const char* hippo_status_string(int status);
+
+/* Bytes of workspace `call` needs for these shapes; never 0 for valid arguments, 0 if they are
+ * invalid.  n_rows = l_txt for SCORE_TOKENS, q_len for the attention calls, ignored otherwise;
+ * seq_len = number of valid cache rows (ctx_len + q_len for attention); k = tokens kept (select);
+ * num_splits as passed to the attention call (0 = library's choice). */
+size_t hippo_workspace_bytes(int32_t call, const hippo_kv_desc* kv, const hippo_video_desc* vid,
+                             int32_t n_rows, int32_t seq_len, int32_t k, int32_t num_splits);
+
+/*
+ * Semantic-aware token scoring (Method, "Semantic-aware Token Preservation", Eq. 2-7).
+ *   s_attn[j] = 1/(H l_txt) sum_h sum_i softmax_j(q_txt[i,h] . K_vid[j] / sqrt(d_k))      (Eq. 2,
+ *               softmax over the N_v visual keys; one layer per call)
+ *   s_temp[j] = 1 - mean over existing neighbour frames f-1, f+1 of the cosine between token j and
+ *               the token at the same grid position there (1 if the video has one frame) (Eq. 3-4)
+ *   s_spa[j]  = population variance over the tokens k of j's crop of cos(emb_j, emb_k)    (Eq. 5-6)
+ *   scores[j] = sum over enabled terms of (s - mean_f) / std_f, statistics per frame, population
+ *               std, a term with std_f = 0 contributes 0                                   (Eq. 7)
+ * A zero-norm embedding has cosine 0 with everything.
+ *
+ * q_txt   [B, l_txt, H, d] contiguous, dtype kv->dtype: the text-prompt queries.
+ * k_cache the cache whose keys guide pruning; rows [vis_offset, vis_offset + N_v) are read.
+ * emb     [B, N_v, emb_dim] with token stride emb_stride_tok (batch stride N_v*emb_stride_tok),
+ *         dtype kv->dtype, or NULL: then token j's embedding is its key vectors of all KV heads
+ *         concatenated in head order (emb_dim, emb_stride_tok ignored).
+ * attn_mass_inout [B, N_v] fp32 or NULL.  If non-NULL it holds the sum of s_attn over the layers
+ *         already processed; this call adds its layer's s_attn to it and, unless ACCUMULATE_ONLY is
+ *         set, uses the accumulated value as the attention term (a positive factor such as 1/N_L
+ *         does not change Eq. 7's normalised value).
+ * scores_out [B, N_v] fp32 (required unless ACCUMULATE_ONLY).
+ * components_out optional [3, B, N_v] fp32: raw s_attn (this call's, or accumulated), s_temp, s_spa.
+ * Errors: NULL_ARG, BAD_SHAPE (l_txt < 1, N_v < 1, vis_offset + N_v > seq_len, crop too large,
+ *         no term enabled), BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
+ */
+int hippo_score_tokens(const void* q_txt, int32_t l_txt,
+                       const void* k_cache, const hippo_kv_desc* kv, int32_t seq_len,
+                       const hippo_video_desc* vid,
+                       const void* emb, int32_t emb_dim, int64_t emb_stride_tok,
+                       uint32_t flags,
+                       float* attn_mass_inout, float* scores_out, float* components_out,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Top-k retention and draft-cache construction (Method, end of "Holistic Score Fusion": keep the
+ * top-k visual tokens by score; App. "Details of Experimental Setups": the pruned video features
+ * are removed from the draft model's input, everything that is not video is kept whole).
+ *   idx_out[b, :] = the k visual-token indices with the largest scores[b, :], listed in ascending
+ *                   index order.  Equal scores (-0 == +0): the lower index wins.  NaN ranks below
+ *                   every number.
+ *   dst rows      = src rows [0, vis_offset) | src rows vis_offset + idx_out[b, .] | src rows
+ *                   [vis_offset + N_v, src_len), for K and V and every KV head, bit copies.
+ * scores [B, N_v] fp32.  1 <= k <= N_v.  src/dst descriptors must agree in batch, n_kv_heads,
+ * head_dim and dtype (strides may differ); dst holds src_len - N_v + k rows.  k_src/v_src may be a
+ * different model's cache than the one that was scored.  k_dst/v_dst may be NULL together to get
+ * the indices only.  src and dst must not overlap.
+ * Errors: NULL_ARG, BAD_SHAPE (k out of range, video span outside src_len, descriptor mismatch),
+ *         BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
+ */
+int hippo_select_gather_kv(const float* scores, int32_t k,
+                           const void* k_src, const void* v_src, const hippo_kv_desc* src,
+                           int32_t src_len, const hippo_video_desc* vid,
+                           void* k_dst, void* v_dst, const hippo_kv_desc* dst,
+                           int32_t* idx_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Target verification attention (Preliminaries, "Speculative Decoding": the target model takes the
+ * prefix plus the gamma draft tokens and emits p_0..p_gamma; Method, "Adaptive Decoding Strategy
+ * Switching": in conservative mode it verifies x_1 alone, so any q_len >= 1 is accepted).
+ *   out[b, i, h, :] = sum_n softmax_n(softmax_scale * q[b,i,h,:] . K[b,h/G,n,:]) V[b,h/G,n,:],
+ *   n in [0, ctx_len + i]   -- the cache already holds the q_len new rows' own K/V at rows
+ *   ctx_len .. ctx_len + q_len - 1, and new row i sees the context and new rows 0..i.
+ * q, out [B, q_len, H, d] contiguous, dtype kv->dtype.  lse_out optional [B, H, q_len] fp32: natural
+ * log of the softmax denominator (of the scaled logits).  softmax_scale <= 0 means 1/sqrt(d).
+ * num_splits: how many slices the KV range is cut into (flash-decoding style), 0 = library's
+ * choice; the result does not depend on it beyond fp32 rounding.  ctx_len >= 0, q_len >= 1.
+ * Errors: NULL_ARG, BAD_SHAPE, BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
+ */
+int hippo_verify_attention(const void* q, int32_t q_len,
+                           const void* k_cache, const void* v_cache, const hippo_kv_desc* kv,
+                           int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                           void* out, float* lse_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Draft-decode attention over the pruned cache (Preliminaries, "Speculative Decoding": the draft
+ * model is invoked gamma times, one new token per forward).  Same contract and arguments as
+ * hippo_verify_attention; the launch heuristics assume q_len = 1 and a short cache.  Running it on
+ * the cache hippo_select_gather_kv built with k = N_v equals attention over the unpruned cache.
+ */
+int hippo_draft_attention(const void* q, int32_t q_len,
+                          const void* k_cache, const void* v_cache, const hippo_kv_desc* kv,
+                          int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                          void* out, float* lse_out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIPPO_H_ */

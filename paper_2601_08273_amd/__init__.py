@@ -1,0 +1,224 @@
+"""Python binding of the HIPPO hot-path library for MI355X (``libhippo.so``, C ABI in include/hippo.h).
+
+Argument marshalling only: every step runs in the HIP kernels.  torch supplies device memory and
+the current stream; nothing here computes.  If the shared library is missing the calls raise -- there
+is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhippo.so")
+
+DTYPE_F32, DTYPE_BF16 = 0, 1
+CALL_SCORE_TOKENS, CALL_SELECT_GATHER_KV, CALL_DRAFT_ATTENTION, CALL_VERIFY_ATTENTION = 0, 1, 2, 3
+SCORE_ATTN, SCORE_TEMP, SCORE_SPA, SCORE_ALL, SCORE_ACCUMULATE_ONLY = 1, 2, 4, 7, 8
+OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = range(7)
+
+EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
+           "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention")
+
+
+class KvDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("dtype", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_n", C.c_int64)]
+
+
+class VideoDesc(C.Structure):
+    _fields_ = [("n_frames", C.c_int32), ("grid_h", C.c_int32), ("grid_w", C.c_int32),
+                ("vis_offset", C.c_int32), ("crop_h", C.c_int32), ("crop_w", C.c_int32)]
+
+
+class HippoError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__("%s failed: status %d (%s)" % (what, status, status_string(status)))
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """dlopen libhippo.so and declare the signatures.  Raises if the library has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libhippo.so is not built: run `python -m paper_2601_08273_amd.build` "
+                           "(there is no fallback implementation)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, u32, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float, C.c_size_t
+    kvp, vdp = C.POINTER(KvDesc), C.POINTER(VideoDesc)
+    lib.hippo_status_string.argtypes = [C.c_int]
+    lib.hippo_status_string.restype = C.c_char_p
+    lib.hippo_workspace_bytes.argtypes = [i32, kvp, vdp, i32, i32, i32, i32]
+    lib.hippo_workspace_bytes.restype = sz
+    lib.hippo_score_tokens.argtypes = [vp, i32, vp, kvp, i32, vdp, vp, i32, i64, u32, vp, vp, vp, vp, sz, vp]
+    lib.hippo_score_tokens.restype = C.c_int
+    lib.hippo_select_gather_kv.argtypes = [vp, i32, vp, vp, kvp, i32, vdp, vp, vp, kvp, vp, vp, sz, vp]
+    lib.hippo_select_gather_kv.restype = C.c_int
+    for fn in (lib.hippo_verify_attention, lib.hippo_draft_attention):
+        fn.argtypes = [vp, i32, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
+        fn.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().hippo_status_string(int(status)).decode()
+
+
+# ---------------------------------------------------------------------------------------------
+# torch plumbing (device memory + streams)
+# ---------------------------------------------------------------------------------------------
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError("unsupported dtype %s (fp32 or bf16)" % t.dtype)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def kv_desc(cache, n_q_heads: int) -> KvDesc:
+    """Descriptor of a [B, H_kv, N, d] cache tensor (any strides with unit stride on d)."""
+    assert cache.dim() == 4 and cache.stride(3) == 1
+    B, Hkv, _, d = cache.shape
+    return KvDesc(B, n_q_heads, Hkv, d, _dtype_code(cache), cache.stride(0), cache.stride(1), cache.stride(2))
+
+
+def video_desc(n_frames, grid_h, grid_w, vis_offset, crop_h=5, crop_w=5) -> VideoDesc:
+    return VideoDesc(n_frames, grid_h, grid_w, vis_offset, crop_h, crop_w)
+
+
+def workspace_bytes(call: int, kv: KvDesc, vid: Optional[VideoDesc], n_rows: int, seq_len: int,
+                    k: int = 0, num_splits: int = 0) -> int:
+    return int(load().hippo_workspace_bytes(call, C.byref(kv), C.byref(vid) if vid is not None else None,
+                                            n_rows, seq_len, k, num_splits))
+
+
+def _workspace(nbytes: int, device, workspace=None):
+    torch = _torch()
+    if workspace is not None:
+        return workspace
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _check(status: int, what: str):
+    if status != OK:
+        raise HippoError(status, what)
+
+
+# ---------------------------------------------------------------------------------------------
+# the four entry points
+# ---------------------------------------------------------------------------------------------
+
+def hippo_score_tokens(q_txt, k_cache, vid: VideoDesc, emb=None, flags: int = SCORE_ALL,
+                       attn_mass_inout=None, want_components: bool = False, scores_out=None, workspace=None,
+                       stream=None):
+    """q_txt [B,L,H,d], k_cache [B,Hkv,N,d] -> scores [B,N_v] fp32 (and components [3,B,N_v])."""
+    torch = _torch()
+    lib = load()
+    assert q_txt.is_contiguous() and q_txt.dim() == 4
+    B, L, H, d = q_txt.shape
+    kv = kv_desc(k_cache, H)
+    n_vis = vid.n_frames * vid.grid_h * vid.grid_w
+    nbytes = workspace_bytes(CALL_SCORE_TOKENS, kv, vid, L, k_cache.shape[2])
+    ws = _workspace(nbytes, q_txt.device, workspace)
+    acc_only = bool(flags & SCORE_ACCUMULATE_ONLY)
+    scores = scores_out
+    if scores is None and not acc_only:
+        scores = torch.empty((B, n_vis), dtype=torch.float32, device=q_txt.device)
+    comps = torch.zeros((3, B, n_vis), dtype=torch.float32, device=q_txt.device) if want_components else None
+    emb_dim, emb_stride = (0, 0) if emb is None else (emb.shape[2], emb.stride(1))
+    if emb is not None:
+        assert emb.dim() == 3 and emb.stride(2) == 1 and emb.stride(0) == emb.shape[1] * emb.stride(1)
+    st = lib.hippo_score_tokens(_ptr(q_txt), L, _ptr(k_cache), C.byref(kv), k_cache.shape[2], C.byref(vid),
+                                _ptr(emb), emb_dim, emb_stride, flags, _ptr(attn_mass_inout), _ptr(scores),
+                                _ptr(comps), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "hippo_score_tokens")
+    return (scores, comps) if want_components else scores
+
+
+def hippo_select_gather_kv(scores, k: int, k_src, v_src, vid: VideoDesc, n_q_heads: Optional[int] = None,
+                           gather: bool = True, idx_out=None, k_dst=None, v_dst=None, workspace=None, stream=None):
+    """scores [B,N_v] fp32 -> (idx [B,k] int32, k_dst, v_dst [B,Hkv,N-N_v+k,d]).
+    idx_out / k_dst / v_dst: optional preallocated outputs (k_dst, v_dst may be strided views)."""
+    torch = _torch()
+    lib = load()
+    assert scores.dtype == torch.float32 and scores.is_contiguous()
+    B, Hkv, N, d = k_src.shape
+    n_vis = vid.n_frames * vid.grid_h * vid.grid_w
+    H = n_q_heads or Hkv
+    src = kv_desc(k_src, H)
+    assert v_src.stride() == k_src.stride() and v_src.shape == k_src.shape
+    idx = idx_out if idx_out is not None else torch.empty((B, k), dtype=torch.int32, device=scores.device)
+    dst = None
+    if gather:
+        n_dst = N - n_vis + k
+        if k_dst is None:
+            k_dst = torch.empty((B, Hkv, max(n_dst, 0), d), dtype=k_src.dtype, device=k_src.device)
+            v_dst = torch.empty_like(k_dst)
+        assert k_dst.shape == (B, Hkv, n_dst, d) and v_dst.shape == k_dst.shape and v_dst.stride() == k_dst.stride()
+        dst = kv_desc(k_dst, H)
+    else:
+        k_dst = v_dst = None
+    ws = _workspace(256, scores.device, workspace)
+    st = lib.hippo_select_gather_kv(_ptr(scores), k, _ptr(k_src), _ptr(v_src), C.byref(src), N, C.byref(vid),
+                                    _ptr(k_dst), _ptr(v_dst), C.byref(dst) if dst is not None else None,
+                                    _ptr(idx), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "hippo_select_gather_kv")
+    return idx, k_dst, v_dst
+
+
+def _attention(fn_name, call, q, k_cache, v_cache, ctx_len, softmax_scale, num_splits, want_lse, out,
+               workspace, stream):
+    torch = _torch()
+    lib = load()
+    assert q.is_contiguous() and q.dim() == 4
+    B, q_len, H, d = q.shape
+    kv = kv_desc(k_cache, H)
+    assert v_cache.stride() == k_cache.stride() and v_cache.shape == k_cache.shape
+    nbytes = workspace_bytes(call, kv, None, q_len, ctx_len + q_len, 0, num_splits)
+    ws = _workspace(nbytes, q.device, workspace)
+    if out is None:
+        out = torch.empty_like(q)
+    lse = torch.empty((B, H, q_len), dtype=torch.float32, device=q.device) if want_lse else None
+    st = getattr(lib, fn_name)(_ptr(q), q_len, _ptr(k_cache), _ptr(v_cache), C.byref(kv), ctx_len,
+                               float(softmax_scale or 0.0), num_splits, _ptr(out), _ptr(lse), _ptr(ws),
+                               ws.numel(), _stream(stream))
+    _check(st, fn_name)
+    return (out, lse) if want_lse else out
+
+
+def hippo_verify_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: float = 0.0, num_splits: int = 0,
+                           want_lse: bool = False, out=None, workspace=None, stream=None):
+    """q [B,q_len,H,d]; caches hold ctx_len+q_len rows; row i attends to [0, ctx_len+i]."""
+    return _attention("hippo_verify_attention", CALL_VERIFY_ATTENTION, q, k_cache, v_cache, ctx_len,
+                      softmax_scale, num_splits, want_lse, out, workspace, stream)
+
+
+def hippo_draft_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: float = 0.0, num_splits: int = 0,
+                          want_lse: bool = False, out=None, workspace=None, stream=None):
+    return _attention("hippo_draft_attention", CALL_DRAFT_ATTENTION, q, k_cache, v_cache, ctx_len,
+                      softmax_scale, num_splits, want_lse, out, workspace, stream)

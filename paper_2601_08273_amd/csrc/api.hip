@@ -1,0 +1,294 @@
+// extern "C" boundary: argument validation, launch heuristics and workspace carving.  No kernel
+// lives here.  Every check runs before the first launch, so a non-zero status means nothing was
+// enqueued.
+#include <math.h>
+
+#include "common.h"
+
+using namespace hippo;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int elem_bytes(int dtype) { return dtype == HIPPO_DTYPE_BF16 ? 2 : 4; }
+
+int check_kv(const hippo_kv_desc* kv) {
+  if (kv == nullptr) return HIPPO_ERR_NULL_ARG;
+  if (kv->dtype != HIPPO_DTYPE_F32 && kv->dtype != HIPPO_DTYPE_BF16) return HIPPO_ERR_BAD_DTYPE;
+  if (kv->batch < 1 || kv->n_kv_heads < 1 || kv->n_q_heads < 1) return HIPPO_ERR_BAD_SHAPE;
+  if (kv->n_q_heads % kv->n_kv_heads != 0) return HIPPO_ERR_BAD_SHAPE;
+  if (kv->head_dim != 64 && kv->head_dim != 128) return HIPPO_ERR_BAD_SHAPE;
+  if (kv->stride_n < kv->head_dim || kv->stride_h < 0 || kv->stride_b < 0) return HIPPO_ERR_BAD_SHAPE;
+  if (kv->batch > 65535 || kv->n_kv_heads > 65535) return HIPPO_ERR_BAD_SHAPE;
+  const int per16 = 16 / elem_bytes(kv->dtype);
+  if (kv->stride_n % per16 || kv->stride_h % per16 || kv->stride_b % per16) return HIPPO_ERR_BAD_ALIGN;
+  return HIPPO_OK;
+}
+
+int check_video(const hippo_video_desc* v) {
+  if (v == nullptr) return HIPPO_ERR_NULL_ARG;
+  if (v->n_frames < 1 || v->grid_h < 1 || v->grid_w < 1 || v->vis_offset < 0) return HIPPO_ERR_BAD_SHAPE;
+  if ((long long)v->n_frames * v->grid_h * v->grid_w > (1ll << 30)) return HIPPO_ERR_BAD_SHAPE;
+  return HIPPO_OK;
+}
+
+// ---- attention planning -------------------------------------------------------------------------
+struct AttnPlan {
+  bool mfma;
+  int R, row_chunk, n_chunks, S;
+  size_t off_m, off_l, bytes;
+};
+
+int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, int num_splits, AttnPlan* pl) {
+  if (q_len < 1 || n_total < q_len || num_splits < 0) return HIPPO_ERR_BAD_SHAPE;
+  const int G = kv->n_q_heads / kv->n_kv_heads;
+  if ((long long)G * q_len > 4096) return HIPPO_ERR_BAD_SHAPE;
+  pl->R = G * q_len;
+  pl->mfma = kv->dtype == HIPPO_DTYPE_BF16;
+  int tile, min_tiles_per_block;
+  if (pl->mfma) {
+    pl->row_chunk = pl->R >= 64 ? 64 : (pl->R + 15) / 16 * 16;
+    tile = 32;
+    min_tiles_per_block = 4;     // one tile for each of the 4 waves
+  } else {
+    pl->row_chunk = 32;
+    tile = 32;
+    min_tiles_per_block = 2;
+  }
+  pl->n_chunks = (pl->R + pl->row_chunk - 1) / pl->row_chunk;
+  if ((long long)kv->batch * pl->n_chunks > 65535) return HIPPO_ERR_BAD_SHAPE;
+  const int n_tiles = (n_total + tile - 1) / tile;
+  int S = num_splits;
+  if (S == 0) {
+    // one block per compute unit (two for the short draft cache, whose blocks are tiny), but
+    // never slices thinner than a tile per wave
+    const long long per_split = (long long)kv->batch * kv->n_kv_heads * pl->n_chunks;
+    const long long target = (call == HIPPO_CALL_DRAFT_ATTENTION) ? kNumCU : kNumCU;
+    S = (int)((target + per_split - 1) / per_split);
+    const int cap = n_tiles / min_tiles_per_block;
+    if (S > cap) S = cap;
+  }
+  if (S > n_tiles) S = n_tiles;
+  if (S < 1) S = 1;
+  if (S > 1024) S = 1024;
+  pl->S = S;
+  const size_t slots = (size_t)kv->batch * kv->n_kv_heads * S;
+  const size_t o_bytes = align_up(slots * pl->R * kv->head_dim * sizeof(float), 256);
+  const size_t ml_bytes = align_up(slots * pl->R * sizeof(float), 256);
+  pl->off_m = o_bytes;
+  pl->off_l = o_bytes + ml_bytes;
+  pl->bytes = o_bytes + 2 * ml_bytes;
+  return HIPPO_OK;
+}
+
+int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache, const void* v_cache,
+                    const hippo_kv_desc* kv, int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                    void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr || workspace == nullptr)
+    return HIPPO_ERR_NULL_ARG;
+  int rc = check_kv(kv);
+  if (rc != HIPPO_OK) return rc;
+  if (ctx_len < 0 || q_len < 1 || (long long)ctx_len + q_len > 0x7fffff00ll) return HIPPO_ERR_BAD_SHAPE;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return HIPPO_ERR_BAD_ALIGN;
+  AttnPlan pl;
+  rc = plan_attention(call, kv, q_len, ctx_len + q_len, num_splits, &pl);
+  if (rc != HIPPO_OK) return rc;
+  if (workspace_bytes < pl.bytes) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
+
+  AttnParams p;
+  p.q = q; p.k = k_cache; p.v = v_cache; p.out = out; p.lse = lse_out;
+  p.part_o = reinterpret_cast<float*>(workspace);
+  p.part_m = reinterpret_cast<float*>(static_cast<char*>(workspace) + pl.off_m);
+  p.part_l = reinterpret_cast<float*>(static_cast<char*>(workspace) + pl.off_l);
+  p.B = kv->batch; p.q_len = q_len; p.H = kv->n_q_heads; p.Hkv = kv->n_kv_heads;
+  p.G = kv->n_q_heads / kv->n_kv_heads; p.R = pl.R;
+  p.ctx_len = ctx_len; p.n_total = ctx_len + q_len;
+  p.sb = kv->stride_b; p.sh = kv->stride_h; p.sn = kv->stride_n;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)kv->head_dim);
+  p.scale_log2 = scale * kLog2e;
+  p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks;
+  const hipError_t e = launch_attention(p, kv->dtype, kv->head_dim, pl.mfma, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
+}
+
+// ---- scoring planning ---------------------------------------------------------------------------
+struct ScorePlan {
+  int n_tile;
+  size_t off_row_l, off_row_lse, off_col, off_sa, off_st, off_ss, bytes;
+};
+
+int plan_score(const hippo_kv_desc* kv, const hippo_video_desc* vid, int l_txt, ScorePlan* pl) {
+  if (l_txt < 1 || l_txt > (1 << 20)) return HIPPO_ERR_BAD_SHAPE;
+  const long long Nv = (long long)vid->n_frames * vid->grid_h * vid->grid_w;
+  const int tile = score_token_tile(kv->dtype);
+  pl->n_tile = (int)((Nv + tile - 1) / tile);
+  if (pl->n_tile > 0x7fffffff / 2) return HIPPO_ERR_BAD_SHAPE;
+  const size_t rows = (size_t)kv->batch * kv->n_q_heads * l_txt;
+  const size_t row_part = align_up(rows * pl->n_tile * sizeof(float), 256);
+  const size_t row_lse = align_up(rows * sizeof(float), 256);
+  const size_t col = align_up((size_t)kv->batch * kv->n_kv_heads * Nv * sizeof(float), 256);
+  const size_t vec = align_up((size_t)kv->batch * Nv * sizeof(float), 256);
+  size_t o = 0;
+  o += row_part;            pl->off_row_l = o;
+  o += row_part;            pl->off_row_lse = o;
+  o += row_lse;             pl->off_col = o;
+  o += col;                 pl->off_sa = o;
+  o += vec;                 pl->off_st = o;
+  o += vec;                 pl->off_ss = o;
+  o += vec;                 pl->bytes = o;
+  return HIPPO_OK;
+}
+
+int check_crop(const hippo_video_desc* vid) {
+  if (vid->crop_h < 1 || vid->crop_w < 1 || (long long)vid->crop_h * vid->crop_w > 64) return HIPPO_ERR_BAD_SHAPE;
+  return HIPPO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hippo_status_string(int status) {
+  switch (status) {
+    case HIPPO_OK: return "ok";
+    case HIPPO_ERR_NULL_ARG: return "a required pointer is NULL";
+    case HIPPO_ERR_BAD_SHAPE: return "invalid size, count, stride or index range";
+    case HIPPO_ERR_BAD_DTYPE: return "unsupported dtype";
+    case HIPPO_ERR_BAD_ALIGN: return "pointer or stride is not 16-byte aligned (workspace: 256)";
+    case HIPPO_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than hippo_workspace_bytes()";
+    case HIPPO_ERR_HIP: return "HIP runtime error at kernel launch";
+    default: return "unknown status";
+  }
+}
+
+size_t hippo_workspace_bytes(int32_t call, const hippo_kv_desc* kv, const hippo_video_desc* vid,
+                             int32_t n_rows, int32_t seq_len, int32_t k, int32_t num_splits) {
+  (void)k;
+  if (check_kv(kv) != HIPPO_OK) return 0;
+  switch (call) {
+    case HIPPO_CALL_SCORE_TOKENS: {
+      ScorePlan pl;
+      if (check_video(vid) != HIPPO_OK || plan_score(kv, vid, n_rows, &pl) != HIPPO_OK) return 0;
+      return pl.bytes;
+    }
+    case HIPPO_CALL_SELECT_GATHER_KV:
+      return 256;   // the selection keeps its state in LDS; a token amount keeps the contract uniform
+    case HIPPO_CALL_DRAFT_ATTENTION:
+    case HIPPO_CALL_VERIFY_ATTENTION: {
+      AttnPlan pl;
+      if (plan_attention(call, kv, n_rows, seq_len, num_splits, &pl) != HIPPO_OK) return 0;
+      return pl.bytes;
+    }
+    default:
+      return 0;
+  }
+}
+
+int hippo_score_tokens(const void* q_txt, int32_t l_txt, const void* k_cache, const hippo_kv_desc* kv,
+                       int32_t seq_len, const hippo_video_desc* vid, const void* emb, int32_t emb_dim,
+                       int64_t emb_stride_tok, uint32_t flags, float* attn_mass_inout, float* scores_out,
+                       float* components_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (q_txt == nullptr || k_cache == nullptr || workspace == nullptr) return HIPPO_ERR_NULL_ARG;
+  int rc = check_kv(kv);
+  if (rc != HIPPO_OK) return rc;
+  if ((rc = check_video(vid)) != HIPPO_OK) return rc;
+  if ((rc = check_crop(vid)) != HIPPO_OK) return rc;
+  const bool acc_only = (flags & HIPPO_SCORE_ACCUMULATE_ONLY) != 0;
+  if (flags & ~(HIPPO_SCORE_ALL | HIPPO_SCORE_ACCUMULATE_ONLY)) return HIPPO_ERR_BAD_SHAPE;
+  if (!acc_only && (flags & HIPPO_SCORE_ALL) == 0) return HIPPO_ERR_BAD_SHAPE;
+  if (acc_only && attn_mass_inout == nullptr) return HIPPO_ERR_NULL_ARG;
+  if (!acc_only && scores_out == nullptr) return HIPPO_ERR_NULL_ARG;
+  const long long Nv = (long long)vid->n_frames * vid->grid_h * vid->grid_w;
+  if (seq_len < 1 || (long long)vid->vis_offset + Nv > seq_len) return HIPPO_ERR_BAD_SHAPE;
+  const int per16 = 16 / elem_bytes(kv->dtype);
+  if (emb != nullptr) {
+    if (emb_dim < 1 || emb_stride_tok < emb_dim) return HIPPO_ERR_BAD_SHAPE;
+    if (emb_dim % per16) return HIPPO_ERR_BAD_SHAPE;
+    if (emb_stride_tok % per16 || !aligned16(emb)) return HIPPO_ERR_BAD_ALIGN;
+  }
+  if (!aligned16(q_txt) || !aligned16(k_cache) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return HIPPO_ERR_BAD_ALIGN;
+  ScorePlan pl;
+  if ((rc = plan_score(kv, vid, l_txt, &pl)) != HIPPO_OK) return rc;
+  if (workspace_bytes < pl.bytes) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
+
+  ScoreParams p;
+  p.q_txt = q_txt; p.k_cache = k_cache; p.emb = emb;
+  p.B = kv->batch; p.L = l_txt; p.H = kv->n_q_heads; p.Hkv = kv->n_kv_heads;
+  p.G = kv->n_q_heads / kv->n_kv_heads; p.D = kv->head_dim; p.dtype = kv->dtype;
+  p.sb = kv->stride_b; p.sh = kv->stride_h; p.sn = kv->stride_n;
+  p.F = vid->n_frames; p.gh = vid->grid_h; p.gw = vid->grid_w; p.P = vid->grid_h * vid->grid_w;
+  p.Nv = (int)Nv; p.vis_off = vid->vis_offset; p.ch = vid->crop_h; p.cw = vid->crop_w;
+  p.emb_dim = emb_dim; p.emb_stride_tok = emb_stride_tok; p.emb_stride_b = Nv * emb_stride_tok;
+  p.flags = flags;
+  p.attn_mass_inout = attn_mass_inout; p.scores_out = scores_out; p.components_out = components_out;
+  char* ws = static_cast<char*>(workspace);
+  p.row_m = reinterpret_cast<float*>(ws);
+  p.row_l = reinterpret_cast<float*>(ws + pl.off_row_l);
+  p.row_lse = reinterpret_cast<float*>(ws + pl.off_row_lse);
+  p.col_part = reinterpret_cast<float*>(ws + pl.off_col);
+  p.s_attn = reinterpret_cast<float*>(ws + pl.off_sa);
+  p.s_temp = reinterpret_cast<float*>(ws + pl.off_st);
+  p.s_spa = reinterpret_cast<float*>(ws + pl.off_ss);
+  p.n_tile = pl.n_tile;
+  const hipError_t e = launch_score(p, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
+}
+
+int hippo_select_gather_kv(const float* scores, int32_t k, const void* k_src, const void* v_src,
+                           const hippo_kv_desc* src, int32_t src_len, const hippo_video_desc* vid,
+                           void* k_dst, void* v_dst, const hippo_kv_desc* dst, int32_t* idx_out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (scores == nullptr || idx_out == nullptr || workspace == nullptr) return HIPPO_ERR_NULL_ARG;
+  int rc = check_video(vid);
+  if (rc != HIPPO_OK) return rc;
+  const long long Nv = (long long)vid->n_frames * vid->grid_h * vid->grid_w;
+  if (k < 1 || k > Nv) return HIPPO_ERR_BAD_SHAPE;
+  const bool do_gather = (k_dst != nullptr) || (v_dst != nullptr);
+  if (do_gather && (k_dst == nullptr || v_dst == nullptr || k_src == nullptr || v_src == nullptr))
+    return HIPPO_ERR_NULL_ARG;
+  if (src == nullptr) return HIPPO_ERR_NULL_ARG;
+  if ((rc = check_kv(src)) != HIPPO_OK) return rc;
+  if (workspace_bytes < 256) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
+  SelectParams p;
+  p.scores = scores; p.B = src->batch; p.Nv = (int)Nv; p.k = k; p.idx_out = idx_out;
+  p.k_src = k_src; p.v_src = v_src; p.k_dst = nullptr; p.v_dst = nullptr;
+  p.Hkv = src->n_kv_heads; p.D = src->head_dim; p.elem_bytes = elem_bytes(src->dtype);
+  p.ssb = src->stride_b; p.ssh = src->stride_h; p.ssn = src->stride_n;
+  p.dsb = p.dsh = p.dsn = 0;
+  p.src_len = src_len; p.dst_len = 0; p.vis_off = vid->vis_offset;
+  if (do_gather) {
+    if (dst == nullptr) return HIPPO_ERR_NULL_ARG;
+    if ((rc = check_kv(dst)) != HIPPO_OK) return rc;
+    if (dst->batch != src->batch || dst->n_kv_heads != src->n_kv_heads || dst->head_dim != src->head_dim ||
+        dst->dtype != src->dtype)
+      return HIPPO_ERR_BAD_SHAPE;
+    if (src_len < 1 || (long long)vid->vis_offset + Nv > src_len) return HIPPO_ERR_BAD_SHAPE;
+    if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_dst) || !aligned16(v_dst))
+      return HIPPO_ERR_BAD_ALIGN;
+    p.k_dst = k_dst; p.v_dst = v_dst;
+    p.dsb = dst->stride_b; p.dsh = dst->stride_h; p.dsn = dst->stride_n;
+    p.dst_len = (int)(src_len - Nv + k);
+  }
+  const hipError_t e = launch_select_gather(p, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
+}
+
+int hippo_verify_attention(const void* q, int32_t q_len, const void* k_cache, const void* v_cache,
+                           const hippo_kv_desc* kv, int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                           void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_entry(HIPPO_CALL_VERIFY_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+int hippo_draft_attention(const void* q, int32_t q_len, const void* k_cache, const void* v_cache,
+                          const hippo_kv_desc* kv, int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                          void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,131 @@
+// Shared device helpers and host-side launch parameter blocks of the HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hippo.h"
+
+namespace hippo {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kNumCU = 256;        // MI355X compute units (8 XCDs x 32)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte load/store
+
+// ---- bf16 <-> fp32 (raw 16-bit patterns; round to nearest even on the way down) ----------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // keep NaN a NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kPerVec = 4;  // elements in one 16-byte vector
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+  static __device__ __forceinline__ void unpack(const u32x4& v, float* o) {
+    o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y);
+    o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
+  }
+};
+template <> struct Elem<uint16_t> {  // bf16 bits
+  static constexpr int kPerVec = 8;
+  static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+  static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
+  static __device__ __forceinline__ void unpack(const u32x4& v, float* o) {
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+    o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
+    o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+};
+
+// ---- wavefront reductions (results valid in every lane) --------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- host side ---------------------------------------------------------------------------------
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// One attention call, as the kernels see it.
+struct AttnParams {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  float* lse;       // may be null
+  float* part_o;    // [B, Hkv, S, R, D] unnormalised partial outputs
+  float* part_m;    // [B, Hkv, S, R] running maxima (log2 domain)
+  float* part_l;    // [B, Hkv, S, R] partial denominators
+  int B, q_len, H, Hkv, G, R;
+  int ctx_len, n_total;
+  long long sb, sh, sn;   // element strides of K and V
+  float scale_log2;       // softmax_scale * log2(e)
+  int S;                  // number of KV splits
+  int row_chunk;          // query rows handled by one block
+  int n_chunks;           // ceil(R / row_chunk)
+};
+
+// Launchers, one per translation unit.  All return a hipError_t from hipGetLastError().
+hipError_t launch_attention(const AttnParams& p, int dtype, int head_dim, bool use_mfma, hipStream_t st);
+
+struct ScoreParams {
+  const void* q_txt;
+  const void* k_cache;
+  const void* emb;       // null => keys concatenated over KV heads
+  int B, L, H, Hkv, G, D, dtype;
+  long long sb, sh, sn;
+  int F, gh, gw, P, Nv, vis_off, ch, cw;
+  int emb_dim;
+  long long emb_stride_tok, emb_stride_b;
+  unsigned flags;
+  float* attn_mass_inout;
+  float* scores_out;
+  float* components_out;
+  // workspace pieces
+  float* row_m;      // [B, H, L, n_tile] partial row maxima
+  float* row_l;      // [B, H, L, n_tile] partial row sums
+  float* row_lse;    // [B, H, L] final log2-domain row normaliser
+  float* col_part;   // [B, Hkv, Nv] per-KV-head column sums
+  float* s_attn;     // [B, Nv]
+  float* s_temp;     // [B, Nv]
+  float* s_spa;      // [B, Nv]
+  int n_tile;        // token tiles of pass 1
+};
+hipError_t launch_score(const ScoreParams& p, hipStream_t st);
+int score_token_tile(int dtype);   // tokens per block in the s_attn passes
+
+struct SelectParams {
+  const float* scores;
+  int B, Nv, k;
+  int32_t* idx_out;
+  const void* k_src;
+  const void* v_src;
+  void* k_dst;
+  void* v_dst;
+  int Hkv, D, elem_bytes;
+  long long ssb, ssh, ssn, dsb, dsh, dsn;   // element strides
+  int src_len, dst_len, vis_off;
+};
+hipError_t launch_select_gather(const SelectParams& p, hipStream_t st);
+
+}  // namespace hippo

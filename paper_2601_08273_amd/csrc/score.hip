@@ -1,0 +1,516 @@
+// Semantic-aware token scoring (paper: Method, "Semantic-aware Token Preservation", Eq. 2-7).
+//
+//   s_attn  (Eq. 2)   two passes over the visual keys: pass 1 finds every text row's softmax
+//                     normaliser over the N_v visual keys, pass 2 recomputes the logits and sums
+//                     exp(z - lse_row) down the columns.  A block owns a tile of tokens (its keys
+//                     stay in registers / LDS) and sweeps all L_txt*G query rows of the KV head.
+//   s_temp, s_spa (Eq. 3-6)  one block per crop: the crop's embeddings and those of the same
+//                     positions in the two neighbouring frames pass through LDS in channel chunks;
+//                     the crop's Gram matrix and the temporal dot products accumulate in registers.
+//   fusion (Eq. 7)    one block per frame: per-term mean / population std, z-scores summed.
+#include "common.h"
+
+namespace hippo {
+
+// =================================================================================================
+// s_attn, vector-ALU version (fp32 inputs).  PASS 1: row statistics; PASS 2: column sums.
+// Block: 32 tokens x all rows (in chunks of 32); thread = (token tid%32, row group tid/32).
+// =================================================================================================
+constexpr int kSaValuTile = 32;
+
+template <typename T, int D, int PASS>
+__global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
+  constexpr int TT = kSaValuTile, RC = 32;
+  constexpr int VPR = D / Elem<T>::kPerVec;
+  __shared__ float Ks[TT][D + 1];
+  __shared__ float Qs[RC][D + 1];
+  __shared__ float lse_s[RC];
+  __shared__ float col_s[8][TT];
+
+  const int tid = threadIdx.x, tok = tid & 31, rg = tid >> 5;
+  const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int n0 = tile * TT;
+  const int Rs = p.L * p.G;
+  const float scale_log2 = rsqrtf((float)D) * kLog2e;
+
+  const T* kbase = (const T*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
+                   (long long)p.vis_off * p.sn;
+  for (int e = tid; e < TT * VPR; e += 256) {
+    const int row = e / VPR, vec = e % VPR, n = n0 + row;
+    float kf[Elem<T>::kPerVec];
+    if (n < p.Nv) {
+      const u32x4 kv4 = *(const u32x4*)(kbase + (long long)n * p.sn + vec * Elem<T>::kPerVec);
+      Elem<T>::unpack(kv4, kf);
+    } else {
+#pragma unroll
+      for (int u = 0; u < Elem<T>::kPerVec; ++u) kf[u] = 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < Elem<T>::kPerVec; ++u) Ks[row][vec * Elem<T>::kPerVec + u] = kf[u];
+  }
+
+  const bool tok_ok = (n0 + tok) < p.Nv;
+  float col = 0.f;
+  for (int r0 = 0; r0 < Rs; r0 += RC) {
+    __syncthreads();
+    for (int e = tid; e < RC * D; e += 256) {
+      const int rr = e / D, c = e % D, r = r0 + rr;
+      float val = 0.f;
+      if (r < Rs) {
+        const int i = r / p.G, gq = r % p.G;
+        val = Elem<T>::load((const T*)p.q_txt + (((long long)b * p.L + i) * p.H + hk * p.G + gq) * D + c);
+      }
+      Qs[rr][c] = val;
+    }
+    if (PASS == 2 && tid < RC) {
+      const int r = r0 + tid;
+      float v = INFINITY;   // padding rows contribute exp2(-inf) = 0
+      if (r < Rs) v = p.row_lse[((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G];
+      lse_s[tid] = v;
+    }
+    __syncthreads();
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < D; ++c) {
+      const float kc = Ks[tok][c];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) s[x] = fmaf(kc, Qs[rg + 8 * x][c], s[x]);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int r = r0 + rg + 8 * x;
+      const float sv = tok_ok ? s[x] * scale_log2 : -INFINITY;
+      if (PASS == 1) {
+        float mx = sv;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        float ps = fast_exp2(sv - mx);      // the tile always holds at least one valid token
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
+        if (tok == 0 && r < Rs) {
+          const long long row = ((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G;
+          p.row_m[row * p.n_tile + tile] = mx;
+          p.row_l[row * p.n_tile + tile] = ps;
+        }
+      } else {
+        col += fast_exp2(sv - lse_s[rg + 8 * x]);
+      }
+    }
+  }
+  if (PASS == 2) {
+    col_s[rg][tok] = col;
+    __syncthreads();
+    if (tid < TT && (n0 + tid) < p.Nv) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) t += col_s[w][tid];
+      p.col_part[((long long)b * p.Hkv + hk) * p.Nv + n0 + tid] = t;
+    }
+  }
+}
+
+// =================================================================================================
+// s_attn, MFMA version (bf16).  Block = 4 waves x 64 tokens; each wave keeps its 64 keys as MFMA A
+// operands in registers for the whole sweep over the query rows, which are staged through LDS in
+// chunks of 64 rows.  Z^T = K Q^T: lane (row j, group g) holds tokens tb*16 + 4g + e.
+// =================================================================================================
+constexpr int kSaMfmaTile = 256;
+
+template <int D, int PASS>
+__global__ __launch_bounds__(256) void sattn_mfma(ScoreParams p) {
+  constexpr int KS = D / 32;
+  constexpr int ROWB = D * 2 + 16;
+  constexpr int CPR = D / 8;
+  constexpr int RCH = 64;               // query rows per LDS chunk
+  __shared__ __align__(16) unsigned char Qs[RCH * ROWB];
+  __shared__ float lse_s[RCH];
+  __shared__ float wm_s[4][RCH];
+  __shared__ float wl_s[4][RCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int n0 = tile * kSaMfmaTile + wave * 64;     // first token of this wave
+  const int Rs = p.L * p.G;
+  const float scale_log2 = rsqrtf((float)D) * kLog2e;
+
+  const uint16_t* kbase = (const uint16_t*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
+                          (long long)p.vis_off * p.sn;
+  // this wave's keys as A operands: token tb*16 + j, head-dim elements (g*KS + ks)*8 .. +8
+  bf16x8 kop[4][KS];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb) {
+    int n = n0 + tb * 16 + j;
+    n = n < p.Nv ? n : p.Nv - 1;                     // in bounds; masked below
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      kop[tb][ks] = *(const bf16x8*)(kbase + (long long)n * p.sn + (g * KS + ks) * 8);
+  }
+  bool tok_ok[4][4];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tok_ok[tb][e] = (n0 + tb * 16 + 4 * g + e) < p.Nv;
+  const bool wave_has_tokens = n0 < p.Nv;
+
+  float col[4][4];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) col[tb][e] = 0.f;
+
+  for (int r0 = 0; r0 < Rs; r0 += RCH) {
+    __syncthreads();
+    for (int e = tid; e < RCH * CPR; e += 256) {
+      const int rr = e / CPR, ch = e % CPR, r = r0 + rr;
+      u32x4 val = (u32x4){0u, 0u, 0u, 0u};
+      if (r < Rs) {
+        const int i = r / p.G, gq = r % p.G;
+        val = *(const u32x4*)((const uint16_t*)p.q_txt +
+                              (((long long)b * p.L + i) * p.H + hk * p.G + gq) * D + ch * 8);
+      }
+      *(u32x4*)(Qs + rr * ROWB + ch * 16) = val;
+    }
+    if (PASS == 2 && tid < RCH) {
+      const int r = r0 + tid;
+      float v = INFINITY;
+      if (r < Rs) v = p.row_lse[((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G];
+      lse_s[tid] = v;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int rb = 0; rb < RCH / 16; ++rb) {
+      f32x4 z[4];
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) z[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 qop = *(const bf16x8*)(Qs + (rb * 16 + j) * ROWB + (g * KS + ks) * 16);
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+          z[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[tb][ks], qop, z[tb], 0, 0, 0);
+      }
+      if (PASS == 1) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            z[tb][e] = tok_ok[tb][e] ? z[tb][e] * scale_log2 : -INFINITY;
+            mx = fmaxf(mx, z[tb][e]);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+        float ps = 0.f;
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ps += fast_exp2(z[tb][e] - m_safe);
+        ps += __shfl_xor(ps, 16, 64);
+        ps += __shfl_xor(ps, 32, 64);
+        if (g == 0) {
+          wm_s[wave][rb * 16 + j] = mx;
+          wl_s[wave][rb * 16 + j] = ps;
+        }
+      } else {
+        const float lse = lse_s[rb * 16 + j];
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) col[tb][e] += fast_exp2(z[tb][e] * scale_log2 - lse);
+      }
+    }
+    if (PASS == 1) {
+      __syncthreads();
+      if (tid < RCH && (r0 + tid) < Rs) {
+        float mm = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mm = fmaxf(mm, wm_s[w][tid]);
+        float ll = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          ll += (wm_s[w][tid] == -INFINITY) ? 0.f : wl_s[w][tid] * fast_exp2(wm_s[w][tid] - mm);
+        const int r = r0 + tid;
+        const long long row = ((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G;
+        p.row_m[row * p.n_tile + tile] = mm;
+        p.row_l[row * p.n_tile + tile] = ll;
+      }
+    }
+  }
+  if (PASS == 2 && wave_has_tokens) {
+    // sum the 16 rows held by the lanes of each group g
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float v = col[tb][e];
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (j == 0 && tok_ok[tb][e])
+          p.col_part[((long long)b * p.Hkv + hk) * p.Nv + n0 + tb * 16 + 4 * g + e] = v;
+      }
+  }
+}
+
+// merge the per-tile row statistics: lse2 = m* + log2(sum_t l_t 2^(m_t - m*))
+__global__ __launch_bounds__(256) void sattn_row_lse(ScoreParams p) {
+  const long long row = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (row >= (long long)p.B * p.H * p.L) return;
+  float mm = -INFINITY;
+  for (int t = 0; t < p.n_tile; ++t) mm = fmaxf(mm, p.row_m[row * p.n_tile + t]);
+  float ll = 0.f;
+  for (int t = 0; t < p.n_tile; ++t) {
+    const float m = p.row_m[row * p.n_tile + t];
+    if (m != -INFINITY) ll += p.row_l[row * p.n_tile + t] * fast_exp2(m - mm);
+  }
+  p.row_lse[row] = mm + __log2f(ll);
+}
+
+// s_attn[b,j] = sum_hk col_part / (H L)  (+ running layer sum)
+__global__ __launch_bounds__(256) void sattn_finalize(ScoreParams p) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long long)p.B * p.Nv) return;
+  const int b = (int)(e / p.Nv), jj = (int)(e % p.Nv);
+  float a = 0.f;
+  for (int hk = 0; hk < p.Hkv; ++hk) a += p.col_part[((long long)b * p.Hkv + hk) * p.Nv + jj];
+  a /= (float)p.H * (float)p.L;
+  if (p.attn_mass_inout != nullptr) {
+    a += p.attn_mass_inout[e];
+    p.attn_mass_inout[e] = a;
+  }
+  p.s_attn[e] = a;
+}
+
+// =================================================================================================
+// s_temp and s_spa: one block per (crop, frame, batch element)
+// =================================================================================================
+constexpr int kEmbChunk = 64;     // channels per LDS pass
+constexpr int kMaxCrop = 64;      // tokens per crop
+
+template <typename T>
+__global__ __launch_bounds__(256) void emb_scores(ScoreParams p) {
+  // E: this frame, previous frame, next frame.  G (the finished Gram matrix) reuses E's storage
+  // once the channel sweep is over.
+  __shared__ float e_raw[3 * kMaxCrop * (kEmbChunk + 1)];
+  float (*E)[kMaxCrop][kEmbChunk + 1] = reinterpret_cast<float (*)[kMaxCrop][kEmbChunk + 1]>(e_raw);
+  float (*G)[kMaxCrop + 1] = reinterpret_cast<float (*)[kMaxCrop + 1]>(e_raw);
+  __shared__ float tdot[4][kMaxCrop];               // v.prev, |prev|^2, v.next, |next|^2
+  __shared__ int tok_s[kMaxCrop];
+
+  const int tid = threadIdx.x;
+  const int ncx = (p.gw + p.cw - 1) / p.cw;
+  const int cy = blockIdx.x / ncx, cx = blockIdx.x % ncx;
+  const int f = blockIdx.y, b = blockIdx.z;
+  const int y0 = cy * p.ch, x0 = cx * p.cw;
+  const int mh = min(p.ch, p.gh - y0), mw = min(p.cw, p.gw - x0);
+  const int M = mh * mw;
+  if (tid < M) tok_s[tid] = f * p.P + (y0 + tid / mw) * p.gw + x0 + tid % mw;
+  const bool has_prev = f > 0, has_next = f + 1 < p.F;
+
+  const int de = p.emb ? p.emb_dim : p.Hkv * p.D;
+  const int n_pairs = M * M;
+  constexpr int PPT = kMaxCrop * kMaxCrop / 256;    // pairs per thread, worst case
+  float gacc[PPT];
+#pragma unroll
+  for (int x = 0; x < PPT; ++x) gacc[x] = 0.f;
+  float tacc = 0.f;                                  // threads [0,4*64): quantity tid/64 of token tid%64
+  __syncthreads();
+
+  constexpr int VPC = kEmbChunk / Elem<T>::kPerVec;  // vectors per chunk row
+  for (int c0 = 0; c0 < de; c0 += kEmbChunk) {
+    // ---- stage chunk [c0, c0+64) of the 3*M vectors ----
+    for (int e = tid; e < 3 * M * VPC; e += 256) {
+      const int which = e / (M * VPC), rem = e % (M * VPC);
+      const int t = rem / VPC, vec = rem % VPC;
+      const int c = c0 + vec * Elem<T>::kPerVec;
+      float vals[Elem<T>::kPerVec];
+#pragma unroll
+      for (int u = 0; u < Elem<T>::kPerVec; ++u) vals[u] = 0.f;
+      const bool present = (which == 0) || (which == 1 && has_prev) || (which == 2 && has_next);
+      if (present && c < de) {
+        const long long tokn = tok_s[t] + (which == 1 ? -p.P : (which == 2 ? p.P : 0));
+        const T* src;
+        if (p.emb) {
+          src = (const T*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok + c;
+        } else {
+          const int hk = c / p.D, cc = c % p.D;
+          src = (const T*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
+                (p.vis_off + tokn) * p.sn + cc;
+        }
+        const u32x4 v4 = *(const u32x4*)src;
+        Elem<T>::unpack(v4, vals);
+      }
+#pragma unroll
+      for (int u = 0; u < Elem<T>::kPerVec; ++u) E[which][t][vec * Elem<T>::kPerVec + u] = vals[u];
+    }
+    __syncthreads();
+    // ---- Gram of the crop ----
+#pragma unroll
+    for (int x = 0; x < PPT; ++x) {
+      const int pr = tid + 256 * x;
+      if (pr < n_pairs) {
+        const int a = pr / M, c2 = pr % M;
+        float s = 0.f;
+#pragma unroll 8
+        for (int c = 0; c < kEmbChunk; ++c) s = fmaf(E[0][a][c], E[0][c2][c], s);
+        gacc[x] += s;
+      }
+    }
+    // ---- temporal dot products and neighbour norms ----
+    {
+      const int qn = tid >> 6, t = tid & 63;
+      if (t < M) {
+        const int other = (qn < 2) ? 1 : 2;
+        const float* ea = (qn & 1) ? E[other][t] : E[0][t];
+        const float* eb = E[other][t];
+        float s = 0.f;
+#pragma unroll 8
+        for (int c = 0; c < kEmbChunk; ++c) s = fmaf(ea[c], eb[c], s);
+        tacc += s;
+      }
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int x = 0; x < PPT; ++x) {
+    const int pr = tid + 256 * x;
+    if (pr < n_pairs) G[pr / M][pr % M] = gacc[x];
+  }
+  tdot[tid >> 6][tid & 63] = tacc;
+  __syncthreads();
+
+  if (tid < M) {
+    const int a = tid;
+    const float na = G[a][a];
+    // spatial: population variance of the cosine row
+    float mu = 0.f;
+    for (int c2 = 0; c2 < M; ++c2) {
+      const float nb = G[c2][c2];
+      const float cs = (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      mu += cs;
+    }
+    mu /= (float)M;
+    float var = 0.f;
+    for (int c2 = 0; c2 < M; ++c2) {
+      const float nb = G[c2][c2];
+      const float cs = (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      var = fmaf(cs - mu, cs - mu, var);
+    }
+    const long long o = (long long)b * p.Nv + tok_s[a];
+    p.s_spa[o] = var / (float)M;
+    // temporal
+    float sum = 0.f;
+    int cnt = 0;
+    if (has_prev) {
+      const float nb = tdot[1][a];
+      sum += (na > 0.f && nb > 0.f) ? tdot[0][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      ++cnt;
+    }
+    if (has_next) {
+      const float nb = tdot[3][a];
+      sum += (na > 0.f && nb > 0.f) ? tdot[2][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      ++cnt;
+    }
+    p.s_temp[o] = 1.f - (cnt ? sum / (float)cnt : 0.f);
+  }
+}
+
+// =================================================================================================
+// Eq. 7: per-frame z-scores, summed over the enabled terms.  One block per (frame, batch element).
+// =================================================================================================
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void fuse_scores(ScoreParams p) {
+  __shared__ float red[4];
+  const int f = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const long long base = (long long)b * p.Nv + (long long)f * p.P;
+  const float* terms[3] = {p.s_attn, p.s_temp, p.s_spa};
+  float mu[3], inv_sigma[3];
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    mu[t] = 0.f;
+    inv_sigma[t] = 0.f;
+    if (!(p.flags & (1u << t))) continue;
+    float s = 0.f;
+    for (int i = tid; i < p.P; i += 256) s += terms[t][base + i];
+    mu[t] = block_sum_256(s, red) / (float)p.P;
+    float v = 0.f;
+    for (int i = tid; i < p.P; i += 256) {
+      const float d = terms[t][base + i] - mu[t];
+      v = fmaf(d, d, v);
+    }
+    const float var = block_sum_256(v, red) / (float)p.P;
+    inv_sigma[t] = var > 0.f ? 1.f / sqrtf(var) : 0.f;
+  }
+  for (int i = tid; i < p.P; i += 256) {
+    float sc = 0.f;
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      if (!(p.flags & (1u << t))) continue;
+      const float x = terms[t][base + i];
+      sc += (x - mu[t]) * inv_sigma[t];
+      if (p.components_out) p.components_out[(long long)t * p.B * p.Nv + base + i] = x;
+    }
+    p.scores_out[base + i] = sc;
+  }
+}
+
+// =================================================================================================
+// host launch
+// =================================================================================================
+int score_token_tile(int dtype) { return dtype == HIPPO_DTYPE_BF16 ? kSaMfmaTile : kSaValuTile; }
+
+template <typename T, int D>
+static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
+  dim3 grid(p.n_tile, p.Hkv, p.B);
+  hipLaunchKernelGGL((sattn_valu<T, D, 1>), grid, dim3(256), 0, st, p);
+  const long long rows = (long long)p.B * p.H * p.L;
+  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((sattn_valu<T, D, 2>), grid, dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st) {
+  dim3 grid(p.n_tile, p.Hkv, p.B);
+  hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(256), 0, st, p);
+  const long long rows = (long long)p.B * p.H * p.L;
+  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((sattn_mfma<D, 2>), grid, dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_score(const ScoreParams& p, hipStream_t st) {
+  hipError_t e = hipSuccess;
+  const bool accumulate_only = (p.flags & HIPPO_SCORE_ACCUMULATE_ONLY) != 0;
+  if ((p.flags & HIPPO_SCORE_ATTN) || accumulate_only) {
+    if (p.dtype == HIPPO_DTYPE_BF16)
+      e = (p.D == 128) ? launch_sattn_mfma<128>(p, st) : launch_sattn_mfma<64>(p, st);
+    else
+      e = (p.D == 128) ? launch_sattn_valu<float, 128>(p, st) : launch_sattn_valu<float, 64>(p, st);
+    if (e != hipSuccess) return e;
+    const long long n = (long long)p.B * p.Nv;
+    hipLaunchKernelGGL(sattn_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if (accumulate_only) return hipSuccess;
+  if (p.flags & (HIPPO_SCORE_TEMP | HIPPO_SCORE_SPA)) {
+    const int ncy = (p.gh + p.ch - 1) / p.ch, ncx = (p.gw + p.cw - 1) / p.cw;
+    dim3 grid(ncy * ncx, p.F, p.B);
+    if (p.dtype == HIPPO_DTYPE_BF16) hipLaunchKernelGGL(emb_scores<uint16_t>, grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(emb_scores<float>, grid, dim3(256), 0, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(fuse_scores, dim3(p.F, p.B), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace hippo

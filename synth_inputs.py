@@ -178,9 +178,8 @@ def make_inputs(cfg: Config, seed: int = 0) -> Dict[str, np.ndarray]:
 
     q_new = _fmt(cfg, rng.standard_normal((B, cfg.q_len, H, d)) * qs)
 
-    k = np.empty((B, hk, n_tot, d), dtype=np.float32)
-    v = (rng.standard_normal((B, hk, n_tot, d)) * inv).astype(np.float32)
-    k[:] = (rng.standard_normal((B, hk, n_tot, d)) * inv).astype(np.float32)
+    v = rng.standard_normal((B, hk, n_tot, d), dtype=np.float32) * np.float32(inv)
+    k = rng.standard_normal((B, hk, n_tot, d), dtype=np.float32) * np.float32(inv)
 
     ring = np.zeros((gh, gw), dtype=bool)
     ring[0, :] = ring[-1, :] = True
@@ -188,8 +187,8 @@ def make_inputs(cfg: Config, seed: int = 0) -> Dict[str, np.ndarray]:
     v0 = cfg.n_prefix
     for b in range(B):
         field = _smooth_field(rng, cfg)                              # [hk,F,gh,gw,d]
-        field += 0.3 * rng.standard_normal(field.shape).astype(np.float32)
-        field *= inv
+        field += np.float32(0.3) * rng.standard_normal(field.shape, dtype=np.float32)
+        field *= np.float32(inv)
         # position bias: +1.5 along the mean text-query direction on the outer ring of each frame
         qm = q_txt[b].astype(np.float64).reshape(cfg.l_txt, hk, G, d).mean(axis=(0, 2))  # [hk,d]
         qm /= np.maximum(np.linalg.norm(qm, axis=-1, keepdims=True), 1e-30)

@@ -1,0 +1,145 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments with the documented status before launching anything.
+Pointers handed over here are fake, aligned, non-null addresses -- they are never dereferenced
+because validation fails first."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2601_08273_amd as h
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # 256-byte aligned, never touched
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(h.LIB_PATH):
+        from paper_2601_08273_amd import build
+        build.build(verbose=False)
+    return h.load()
+
+
+def test_exports_match_header(lib):
+    text = open(os.path.join(ROOT, "include", "hippo.h")).read()
+    declared = set(re.findall(r"\b(hippo_[a-z_]+)\s*\(", text))
+    assert declared == set(h.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(h.KvDesc) == 48 and h.KvDesc.stride_b.offset == 24
+    assert C.sizeof(h.VideoDesc) == 24
+
+
+def test_status_strings(lib):
+    seen = {h.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and h.status_string(0) == "ok"
+    assert "unknown" in h.status_string(99)
+
+
+def _kv(**kw):
+    d = dict(batch=1, n_q_heads=28, n_kv_heads=4, head_dim=128, dtype=h.DTYPE_BF16)
+    d.update(kw)
+    n = 20000
+    d.setdefault("stride_n", d["head_dim"])
+    d.setdefault("stride_h", n * d["head_dim"])
+    d.setdefault("stride_b", d["n_kv_heads"] * n * d["head_dim"])
+    return h.KvDesc(**d)
+
+
+def _verify(lib, kv, q_len=6, ctx=16640, ws_bytes=1 << 30, q=FAKE, k=FAKE, v=FAKE, out=FAKE, ws=FAKE, splits=0,
+            fn="hippo_verify_attention"):
+    return getattr(lib, fn)(q, q_len, k, v, C.byref(kv), ctx, 0.0, splits, out, None, ws, ws_bytes, None)
+
+
+def test_attention_argument_errors(lib):
+    kv = _kv()
+    for fn in ("hippo_verify_attention", "hippo_draft_attention"):
+        assert _verify(lib, kv, q=None, fn=fn) == h.ERR_NULL_ARG
+        assert _verify(lib, kv, out=None, fn=fn) == h.ERR_NULL_ARG
+        assert _verify(lib, kv, ws=None, fn=fn) == h.ERR_NULL_ARG
+        assert _verify(lib, kv, q_len=0, fn=fn) == h.ERR_BAD_SHAPE
+        assert _verify(lib, kv, ctx=-1, fn=fn) == h.ERR_BAD_SHAPE
+        assert _verify(lib, kv, splits=-2, fn=fn) == h.ERR_BAD_SHAPE
+        assert _verify(lib, kv, k=FAKE + 8, fn=fn) == h.ERR_BAD_ALIGN
+        assert _verify(lib, kv, ws=FAKE + 16, fn=fn) == h.ERR_BAD_ALIGN
+        assert _verify(lib, kv, ws_bytes=1024, fn=fn) == h.ERR_WORKSPACE_TOO_SMALL
+    assert _verify(lib, _kv(dtype=7)) == h.ERR_BAD_DTYPE
+    assert _verify(lib, _kv(head_dim=96)) == h.ERR_BAD_SHAPE
+    assert _verify(lib, _kv(n_q_heads=30)) == h.ERR_BAD_SHAPE          # not a multiple of n_kv_heads
+    assert _verify(lib, _kv(stride_n=64)) == h.ERR_BAD_SHAPE           # rows overlap
+    assert _verify(lib, _kv(stride_n=132)) == h.ERR_BAD_ALIGN          # 264-byte rows
+    assert lib.hippo_verify_attention(FAKE, 6, FAKE, FAKE, None, 10, 0.0, 0, FAKE, None, FAKE, 1 << 20, None) \
+        == h.ERR_NULL_ARG
+
+
+def test_workspace_query(lib):
+    kv = _kv()
+    need = h.workspace_bytes(h.CALL_VERIFY_ATTENTION, kv, None, 6, 16646)
+    assert need > 0 and need % 256 == 0
+    assert _verify(lib, kv, ws_bytes=need - 1) == h.ERR_WORKSPACE_TOO_SMALL
+    # more splits need more room; explicit split count is honoured by the query
+    assert h.workspace_bytes(h.CALL_VERIFY_ATTENTION, kv, None, 6, 16646, 0, 128) > \
+        h.workspace_bytes(h.CALL_VERIFY_ATTENTION, kv, None, 6, 16646, 0, 8)
+    assert h.workspace_bytes(h.CALL_VERIFY_ATTENTION, _kv(dtype=9), None, 6, 16646) == 0
+    assert h.workspace_bytes(42, kv, None, 6, 16646) == 0
+    vid = h.video_desc(64, 16, 16, 128)
+    assert h.workspace_bytes(h.CALL_SCORE_TOKENS, kv, vid, 128, 16646) > 0
+    assert h.workspace_bytes(h.CALL_SCORE_TOKENS, kv, None, 128, 16646) == 0
+    assert h.workspace_bytes(h.CALL_SELECT_GATHER_KV, kv, vid, 0, 16646, 1639) >= 256
+
+
+def _score(lib, kv, vid, l_txt=128, seq_len=16646, flags=h.SCORE_ALL, q=FAKE, k=FAKE, emb=None, emb_dim=0,
+           emb_stride=0, mass=None, scores=FAKE, ws=FAKE, ws_bytes=1 << 32):
+    return lib.hippo_score_tokens(q, l_txt, k, C.byref(kv), seq_len, C.byref(vid), emb, emb_dim, emb_stride,
+                                  flags, mass, scores, None, ws, ws_bytes, None)
+
+
+def test_score_argument_errors(lib):
+    kv, vid = _kv(), h.video_desc(64, 16, 16, 128)
+    assert _score(lib, kv, vid, q=None) == h.ERR_NULL_ARG
+    assert _score(lib, kv, vid, scores=None) == h.ERR_NULL_ARG
+    assert _score(lib, kv, vid, flags=h.SCORE_ACCUMULATE_ONLY, mass=None) == h.ERR_NULL_ARG
+    assert _score(lib, kv, vid, flags=0) == h.ERR_BAD_SHAPE
+    assert _score(lib, kv, vid, flags=64) == h.ERR_BAD_SHAPE
+    assert _score(lib, kv, vid, l_txt=0) == h.ERR_BAD_SHAPE
+    assert _score(lib, kv, vid, seq_len=16000) == h.ERR_BAD_SHAPE               # video runs past the cache
+    assert _score(lib, kv, h.video_desc(64, 16, 16, 128, 9, 9)) == h.ERR_BAD_SHAPE   # 81-token crops
+    assert _score(lib, kv, h.video_desc(0, 16, 16, 128)) == h.ERR_BAD_SHAPE
+    assert _score(lib, kv, vid, emb=FAKE, emb_dim=100, emb_stride=104) == h.ERR_BAD_SHAPE   # dim % 8
+    assert _score(lib, kv, vid, emb=FAKE, emb_dim=512, emb_stride=516) == h.ERR_BAD_ALIGN
+    assert _score(lib, kv, vid, emb=FAKE + 2, emb_dim=512, emb_stride=512) == h.ERR_BAD_ALIGN
+    assert _score(lib, kv, vid, ws_bytes=4096) == h.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_select_argument_errors(lib):
+    kv, vid = _kv(), h.video_desc(64, 16, 16, 128)
+
+    def call(k=1639, scores=FAKE, idx=FAKE, ksrc=FAKE, vsrc=FAKE, kdst=FAKE, vdst=FAKE, src=kv, dst=kv,
+             src_len=16646, ws_bytes=256):
+        return lib.hippo_select_gather_kv(scores, k, ksrc, vsrc, C.byref(src) if src else None, src_len,
+                                          C.byref(vid), kdst, vdst, C.byref(dst) if dst else None, idx, FAKE,
+                                          ws_bytes, None)
+    assert call(scores=None) == h.ERR_NULL_ARG
+    assert call(idx=None) == h.ERR_NULL_ARG
+    assert call(vdst=None) == h.ERR_NULL_ARG                    # K without V
+    assert call(src=None) == h.ERR_NULL_ARG
+    assert call(dst=None) == h.ERR_NULL_ARG
+    assert call(k=0) == h.ERR_BAD_SHAPE
+    assert call(k=16385) == h.ERR_BAD_SHAPE
+    assert call(src_len=16000) == h.ERR_BAD_SHAPE
+    assert call(dst=_kv(head_dim=64)) == h.ERR_BAD_SHAPE
+    assert call(dst=_kv(dtype=h.DTYPE_F32)) == h.ERR_BAD_SHAPE
+    assert call(kdst=FAKE + 4) == h.ERR_BAD_ALIGN
+    assert call(ws_bytes=16) == h.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_binding_refuses_missing_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(h, "_lib", None)
+    monkeypatch.setattr(h, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        h.load()

@@ -1,0 +1,153 @@
+"""GPU parity: hippo_verify_attention / hippo_draft_attention (through the C ABI) vs the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from gpu_util import assert_close, dev, host, prep
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(hippo, q, k, v, ctx, dtype, num_splits=0, scale=0.0, fn="verify", check_lse=True, what=""):
+    q, k, v = prep(q, dtype), prep(k, dtype), prep(v, dtype)
+    f = hippo.hippo_verify_attention if fn == "verify" else hippo.hippo_draft_attention
+    out, lse = f(dev(q, dtype), dev(k, dtype), dev(v, dtype), ctx, softmax_scale=scale, num_splits=num_splits,
+                 want_lse=True)
+    torch.cuda.synchronize()
+    ro, rl = oracle.attention(q, k, v, ctx, scale if scale > 0 else None)
+    assert_close(host(out), ro, dtype, what + " out")
+    if check_lse:
+        np.testing.assert_allclose(host(lse), rl, rtol=2e-5, atol=2e-5, err_msg=what + " lse")
+    return host(out)
+
+
+def rand_case(seed, B, ql, H, Hkv, d, ctx, qscale=1.0, extra_rows=0):
+    r = np.random.default_rng(seed)
+    q = r.standard_normal((B, ql, H, d)) * qscale
+    n = ctx + ql + extra_rows
+    k = r.standard_normal((B, Hkv, n, d))
+    v = r.standard_normal((B, Hkv, n, d))
+    return q, k, v
+
+
+@pytest.mark.parametrize("name", ["tiny", "draft"])
+@pytest.mark.parametrize("num_splits", [0, 1, 3, 16])
+def test_verify_on_configs(hippo, name, num_splits):
+    cfg = si.CONFIGS[name]
+    x = si.make_inputs(cfg, 0)
+    run_case(hippo, x["q_new"], x["k"], x["v"], cfg.ctx_len, cfg.dtype, num_splits, what=name)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("shape", [
+    # B, q_len, H, Hkv, d, ctx
+    (1, 1, 4, 4, 64, 1),          # single context row, MHA
+    (2, 3, 8, 2, 64, 37),         # ragged, shorter than one tile
+    (1, 9, 7, 1, 128, 333),       # R = 63, one KV head
+    (2, 5, 16, 2, 128, 1000),     # R = 40
+    (1, 6, 28, 4, 128, 2049),     # headline head geometry, tile-boundary tail
+    (1, 2, 6, 2, 64, 0),          # empty context: rows see only the new tokens
+    (1, 12, 16, 2, 64, 515),      # R = 96 > 64: more than one row chunk
+])
+def test_verify_random_shapes_sharp_softmax(hippo, dtype, shape):
+    B, ql, H, Hkv, d, ctx = shape
+    # logits of std ~3: a handful of keys dominate each row, so a wrong mask or a dropped tile shows
+    q, k, v = rand_case(hash(shape) % 1000, B, ql, H, Hkv, d, ctx, qscale=3.0)
+    for s in (0, 2):
+        run_case(hippo, q, k, v, ctx, dtype, s, what="%s %s S=%d" % (dtype, shape, s))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_causal_mask_probe_with_one_hot_values(hippo, dtype):
+    # V = identity: the output IS the probability row.  Mass beyond ctx+i must be exactly zero.
+    B, ql, H, Hkv, d, ctx = 1, 6, 4, 2, 128, 100
+    n = ctx + ql
+    q, k, _ = rand_case(5, B, ql, H, Hkv, d, ctx)
+    v = np.zeros((B, Hkv, n, d), np.float32)
+    v[:, :, np.arange(n), np.arange(n)] = 1.0
+    out = run_case(hippo, q, k, v, ctx, dtype, what="probe")
+    for i in range(ql):
+        assert np.all(out[0, i, :, ctx + i + 1:] == 0.0)
+        np.testing.assert_allclose(out[0, i].sum(-1), 1.0, atol=2e-2 if dtype == "bf16" else 1e-5)
+    ones = run_case(hippo, q, k, np.ones_like(v), ctx, dtype, what="rows sum to 1")
+    np.testing.assert_allclose(ones, 1.0, atol=8e-3 if dtype == "bf16" else 1e-6)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gamma0_is_single_token_decode_and_rows_match_truncated_calls(hippo, dtype):
+    B, ql, H, Hkv, d, ctx = 1, 5, 8, 2, 64, 300
+    q, k, v = rand_case(7, B, ql, H, Hkv, d, ctx, qscale=2.0)
+    full = run_case(hippo, q, k, v, ctx, dtype, what="full")
+    for i in range(ql):
+        for fn in ("verify", "draft"):
+            one = run_case(hippo, q[:, i:i + 1], k[:, :, :ctx + i + 1], v[:, :, :ctx + i + 1], ctx + i, dtype,
+                           fn=fn, what="row %d via %s" % (i, fn))
+            assert_close(one[:, 0], full[:, i].astype(np.float64), dtype, "row %d vs verify row" % i)
+
+
+def test_split_count_does_not_change_the_result(hippo):
+    cfg = si.CONFIGS["draft"]
+    x = si.make_inputs(cfg, 1)
+    outs = [run_case(hippo, x["q_new"], x["k"], x["v"], cfg.ctx_len, cfg.dtype, s, what="S=%d" % s)
+            for s in (1, 2, 5, 33, 132)]
+    for o in outs[1:]:
+        assert np.max(np.abs(o - outs[0])) <= 2 ** -7 * np.max(np.abs(outs[0])) + 1e-6
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_strided_caches_and_custom_scale(hippo, dtype):
+    # K and V interleaved in one allocation ([B,Hkv,N_alloc,2,d]): stride_n = 2d, oversized stride_h
+    B, ql, H, Hkv, d, ctx = 2, 4, 6, 3, 64, 150
+    q, k, v = rand_case(11, B, ql, H, Hkv, d, ctx)
+    q, k, v = prep(q, dtype), prep(k, dtype), prep(v, dtype)
+    n, n_alloc = ctx + ql, ctx + ql + 13
+    buf = torch.zeros((B, Hkv, n_alloc, 2, d), dtype=dev(q, dtype).dtype, device="cuda")
+    buf[:, :, :n, 0] = dev(k, dtype)
+    buf[:, :, :n, 1] = dev(v, dtype)
+    kd, vd = buf[:, :, :, 0], buf[:, :, :, 1]
+    assert kd.stride(2) == 2 * d
+    out = hippo.hippo_verify_attention(dev(q, dtype), kd, vd, ctx, softmax_scale=0.21)
+    torch.cuda.synchronize()
+    ro, _ = oracle.attention(q, k, v, ctx, 0.21)
+    assert_close(host(out), ro, dtype, "strided")
+
+
+def test_draft_attention_on_full_keep_equals_unpruned(hippo):
+    cfg = si.CONFIGS["draft"]
+    x = si.make_inputs(cfg, 2)
+    dt = cfg.dtype
+    kd, vd = dev(x["k"], dt), dev(x["v"], dt)
+    q1 = dev(x["q_new"][:, :1], dt)
+    vid = hippo.video_desc(cfg.n_frames, cfg.grid_h, cfg.grid_w, cfg.n_prefix)
+    scores = torch.zeros((cfg.batch, cfg.n_visual), dtype=torch.float32, device="cuda")
+    n = cfg.ctx_len + 1
+    idx, kp, vp = hippo.hippo_select_gather_kv(scores, cfg.n_visual, kd[:, :, :n], vd[:, :, :n], vid, cfg.n_q_heads)
+    a = hippo.hippo_draft_attention(q1, kp, vp, cfg.ctx_len)
+    b = hippo.hippo_draft_attention(q1, kd, vd, cfg.ctx_len)
+    torch.cuda.synchronize()
+    assert torch.equal(kp, kd[:, :, :n]) and torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["c3_16k", "c4_long"])
+def test_verify_full_size(hippo, name):
+    """The benchmark shapes, in the launch configuration bench.py times (library-chosen splits)."""
+    cfg = si.CONFIGS[name]
+    x = si.make_inputs(cfg, 0)
+    run_case(hippo, x["q_new"], x["k"], x["v"], cfg.ctx_len, cfg.dtype, 0, what=name)
+
+
+def test_verify_full_size_large_share_sampled(hippo):
+    """Batch 4 x 8 KV heads x 37K rows: GPU runs everything, the oracle checks two batch elements."""
+    cfg = si.CONFIGS["c5_large"]
+    x = si.make_inputs(cfg, 0)
+    dt = cfg.dtype
+    out = hippo.hippo_verify_attention(dev(x["q_new"], dt), dev(x["k"], dt), dev(x["v"], dt), cfg.ctx_len)
+    torch.cuda.synchronize()
+    got = host(out)
+    for b in (0, 3):
+        ro, _ = oracle.attention(x["q_new"][b:b + 1], x["k"][b:b + 1], x["v"][b:b + 1], cfg.ctx_len)
+        assert_close(got[b:b + 1], ro, dt, "c5 batch %d" % b)

@@ -1,0 +1,180 @@
+"""GPU parity: hippo_score_tokens and hippo_select_gather_kv (through the C ABI) vs the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from gpu_util import assert_close, assert_indices_consistent, dev, host, prep
+
+pytestmark = pytest.mark.gpu
+
+
+def score_case(hippo, q_txt, k, vis_off, F, gh, gw, dtype, ch=5, cw=5, emb=None, flags=7, what=""):
+    q_txt, k = prep(q_txt, dtype), prep(k, dtype)
+    emb_h = None if emb is None else prep(emb, dtype)
+    vid = hippo.video_desc(F, gh, gw, vis_off, ch, cw)
+    scores, comps = hippo.hippo_score_tokens(dev(q_txt, dtype), dev(k, dtype), vid,
+                                             emb=None if emb is None else dev(emb_h, dtype), flags=flags,
+                                             want_components=True)
+    torch.cuda.synchronize()
+    rs, rc = oracle.score_tokens(q_txt, k, vis_off, F, gh, gw, ch, cw, emb=emb_h, flags=flags)
+    names = ["s_attn", "s_temp", "s_spa"]
+    for t in range(3):
+        if flags & (1 << t):
+            assert_close(host(comps[t]), rc[t], dtype, "%s %s" % (what, names[t]))
+    # the fused score is a sum of z-scores of O(1); its error is judged against O(1), i.e. the
+    # tolerance's rms floor (z-scores cross zero)
+    assert_close(host(scores), rs, dtype, what + " fused")
+    return host(scores), rs
+
+
+@pytest.mark.parametrize("name", ["tiny", "draft"])
+def test_score_on_configs(hippo, name):
+    cfg = si.CONFIGS[name]
+    x = si.make_inputs(cfg, 0)
+    n = cfg.ctx_len
+    score_case(hippo, x["q_txt"], x["k"][:, :, :n], cfg.n_prefix, cfg.n_frames, cfg.grid_h, cfg.grid_w,
+               cfg.dtype, what=name)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("shape", [
+    # B, L, H, Hkv, d, F, gh, gw, vis_off, tail, crop
+    (1, 3, 2, 1, 64, 1, 5, 5, 0, 0, (5, 5)),       # one frame: s_temp = 1 everywhere -> sigma 0
+    (2, 7, 6, 2, 64, 2, 7, 9, 3, 2, (5, 5)),       # two frames: every frame has one neighbour
+    (1, 33, 8, 2, 128, 5, 6, 11, 17, 5, (4, 3)),   # odd everything, 4x3 crops
+    (1, 70, 7, 1, 128, 3, 13, 21, 8, 8, (5, 5)),   # 819 tokens: several tiles and a ragged tail
+    (2, 5, 4, 4, 64, 4, 8, 8, 1, 0, (8, 8)),       # 64-token crops (the maximum)
+])
+def test_score_random_shapes(hippo, dtype, shape):
+    B, L, H, Hkv, d, F, gh, gw, off, tail, (ch, cw) = shape
+    r = np.random.default_rng(sum(shape[:10]))
+    nv = F * gh * gw
+    q = r.standard_normal((B, L, H, d)) * 1.5
+    k = r.standard_normal((B, Hkv, off + nv + tail, d))
+    # correlate neighbouring frames and neighbouring patches a little so the terms have structure
+    kv = k[:, :, off:off + nv].reshape(B, Hkv, F, gh, gw, d)
+    kv += 0.8 * np.roll(kv, 1, axis=2) + 0.5 * np.roll(kv, 1, axis=4)
+    score_case(hippo, q, k, off, F, gh, gw, dtype, ch, cw, what="%s %s" % (dtype, shape))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_score_explicit_embedding_and_flags(hippo, dtype):
+    B, L, H, Hkv, d, F, gh, gw, off = 1, 9, 4, 2, 64, 3, 6, 7, 4
+    r = np.random.default_rng(21)
+    nv = F * gh * gw
+    q = r.standard_normal((B, L, H, d))
+    k = r.standard_normal((B, Hkv, off + nv + 3, d))
+    emb = r.standard_normal((B, nv, 200))         # 200 channels: 3 chunks of 64 and a tail of 8
+    emb[:, gh * gw:2 * gh * gw] += 0.7 * emb[:, :gh * gw]
+    for flags in (7, 1, 2, 4, 6, 5):
+        score_case(hippo, q, k, off, F, gh, gw, dtype, emb=emb, flags=flags, what="flags %d" % flags)
+
+
+def test_score_layer_accumulation(hippo):
+    """Outer layer sum of Eq. 2: two ACCUMULATE_ONLY-style calls; the last one fuses."""
+    cfg = si.CONFIGS["tiny"]
+    xs = [si.make_inputs(cfg, s) for s in (0, 1)]
+    vid = hippo.video_desc(cfg.n_frames, cfg.grid_h, cfg.grid_w, cfg.n_prefix)
+    mass = torch.zeros((cfg.batch, cfg.n_visual), dtype=torch.float32, device="cuda")
+    k0 = dev(xs[0]["k"], cfg.dtype)
+    hippo.hippo_score_tokens(dev(xs[0]["q_txt"], cfg.dtype), k0, vid, flags=hippo.SCORE_ACCUMULATE_ONLY,
+                             attn_mass_inout=mass)
+    # second layer: its own queries/keys for the attention term; embeddings come from this call's keys
+    scores, comps = hippo.hippo_score_tokens(dev(xs[1]["q_txt"], cfg.dtype), dev(xs[1]["k"], cfg.dtype), vid,
+                                             attn_mass_inout=mass, want_components=True)
+    torch.cuda.synchronize()
+    sa = sum(oracle.s_attn(x["q_txt"], x["k"], cfg.n_prefix, cfg.n_visual) for x in xs)
+    assert_close(host(mass), sa, "fp32", "accumulated mass")
+    emb = oracle.keys_as_embedding(xs[1]["k"], cfg.n_prefix, cfg.n_visual)
+    ref = oracle.fuse(sa, oracle.s_temp(emb, cfg.n_frames),
+                      oracle.s_spa(emb, cfg.n_frames, cfg.grid_h, cfg.grid_w), cfg.n_frames)
+    assert_close(host(scores), ref, "fp32", "fused after accumulation")
+
+
+# ---------------------------------------------------------------------------------------------
+# selection + gather: bit exact
+# ---------------------------------------------------------------------------------------------
+
+def select_case(hippo, scores: np.ndarray, k: int):
+    B, n = scores.shape
+    vid = hippo.video_desc(1, 1, n, 0)
+    dummy = torch.zeros((B, 1, n, 64), dtype=torch.float32, device="cuda")
+    idx, _, _ = hippo.hippo_select_gather_kv(torch.from_numpy(scores).cuda(), k, dummy, dummy, vid, gather=False)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx.cpu().numpy(), oracle.topk(scores, k))
+
+
+@pytest.mark.parametrize("n,k", [(1, 1), (63, 7), (64, 64), (1025, 100), (4096, 410), (16384, 1639),
+                                 (36864, 3687), (36864, 36863), (5000, 1)])
+def test_topk_bit_exact(hippo, n, k):
+    select_case(hippo, si.random_scores(2, n, n + k), k)
+
+
+@pytest.mark.parametrize("n,k,distinct", [(1000, 100, 3), (4096, 2048, 2), (777, 776, 1), (20000, 5000, 17)])
+def test_topk_with_many_ties(hippo, n, k, distinct):
+    select_case(hippo, si.random_scores(3, n, n, n_distinct=distinct), k)
+
+
+def test_topk_special_values(hippo):
+    s = si.random_scores(4, 3000, 9)
+    s[0, ::5] = np.nan
+    s[0, 1::7] = -np.inf
+    s[1, ::2] = 0.0
+    s[1, 1::4] = -0.0
+    s[2, :] = np.inf
+    s[3, ::3] = np.float32(1e-45)          # denormals order like any other number
+    s[3, 1::3] = -np.float32(1e-45)
+    for k in (1, 299, 1500, 2999, 3000):
+        select_case(hippo, s, k)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gather_bit_exact(hippo, dtype):
+    B, Hkv, d, F, gh, gw, off, tail, k = 2, 3, 128, 3, 5, 7, 6, 9, 31
+    nv = F * gh * gw
+    r = np.random.default_rng(3)
+    ks = prep(r.standard_normal((B, Hkv, off + nv + tail, d)), dtype)
+    vs = prep(r.standard_normal((B, Hkv, off + nv + tail, d)), dtype)
+    scores = si.random_scores(B, nv, 4, n_distinct=11)
+    vid = hippo.video_desc(F, gh, gw, off)
+    idx, kd, vd = hippo.hippo_select_gather_kv(torch.from_numpy(scores).cuda(), k, dev(ks, dtype), dev(vs, dtype), vid)
+    torch.cuda.synchronize()
+    ridx = oracle.topk(scores, k)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_array_equal(host(kd), oracle.gather(ks, off, nv, ridx))
+    np.testing.assert_array_equal(host(vd), oracle.gather(vs, off, nv, ridx))
+
+
+# ---------------------------------------------------------------------------------------------
+# end to end: score -> select -> gather -> draft attention on the pruned cache
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny", "draft", "c3_16k"])
+def test_prune_pipeline(hippo, name):
+    cfg = si.CONFIGS[name]
+    x = si.make_inputs(cfg, 0)
+    dt = cfg.dtype
+    n = cfg.ctx_len
+    kd, vd = dev(x["k"][:, :, :n], dt), dev(x["v"][:, :, :n], dt)
+    vid = hippo.video_desc(cfg.n_frames, cfg.grid_h, cfg.grid_w, cfg.n_prefix)
+    scores = hippo.hippo_score_tokens(dev(x["q_txt"], dt), kd, vid)
+    idx, kp, vp = hippo.hippo_select_gather_kv(scores, cfg.k_keep, kd, vd, vid, cfg.n_q_heads)
+    torch.cuda.synchronize()
+    # selection is bit exact given the GPU's own fp32 scores ...
+    np.testing.assert_array_equal(idx.cpu().numpy(), oracle.topk(host(scores), cfg.k_keep))
+    # ... and agrees with the all-oracle selection except for near-ties at the threshold
+    rs, _ = oracle.score_tokens(x["q_txt"], x["k"][:, :, :n], cfg.n_prefix, cfg.n_frames, cfg.grid_h, cfg.grid_w)
+    assert_close(host(scores), rs, dt, name + " scores")
+    ridx = oracle.topk(rs.astype(np.float32), cfg.k_keep)
+    assert_indices_consistent(idx.cpu().numpy(), rs, ridx, tol=1e-4 if dt == "fp32" else 5e-2)
+    # the pruned cache is what the oracle builds from the same indices
+    np.testing.assert_array_equal(host(kp), oracle.gather(x["k"][:, :, :n], cfg.n_prefix, cfg.n_visual, idx.cpu().numpy()))
+    # draft decode over it: the draft cache holds the pruned context plus the new token's own row
+    kpn = torch.cat([kp, dev(x["k"][:, :, n:n + 1], dt)], dim=2)
+    vpn = torch.cat([vp, dev(x["v"][:, :, n:n + 1], dt)], dim=2)
+    out = hippo.hippo_draft_attention(dev(x["q_new"][:, :1], dt), kpn, vpn, kp.shape[2])
+    torch.cuda.synchronize()
+    ro, _ = oracle.attention(x["q_new"][:, :1], host(kpn), host(vpn), kp.shape[2])
+    assert_close(host(out), ro, dt, name + " draft attention")
