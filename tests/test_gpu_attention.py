@@ -21,7 +21,10 @@ def run_case(hippo, q, k, v, ctx, dtype, num_splits=0, scale=0.0, fn="verify", c
     ro, rl = oracle.attention(q, k, v, ctx, scale if scale > 0 else None)
     assert_close(host(out), ro, dtype, what + " out")
     if check_lse:
-        np.testing.assert_allclose(host(lse), rl, rtol=2e-5, atol=2e-5, err_msg=what + " lse")
+        # bf16 path: the denominator sums the bf16-rounded probabilities the PV product uses
+        # (relative 2^-9 each), so ln(denominator) is off by at most 2^-9
+        tol = 2e-5 if dtype == "fp32" else 2.0 ** -9
+        np.testing.assert_allclose(host(lse), rl, rtol=tol, atol=tol, err_msg=what + " lse")
     return host(out)
 
 
