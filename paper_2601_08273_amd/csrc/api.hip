@@ -20,6 +20,7 @@ int check_kv(const hippo_kv_desc* kv) {
   if (kv->n_q_heads % kv->n_kv_heads != 0) return HIPPO_ERR_BAD_SHAPE;
   if (kv->head_dim != 64 && kv->head_dim != 128) return HIPPO_ERR_BAD_SHAPE;
   if (kv->stride_n < kv->head_dim || kv->stride_h < 0 || kv->stride_b < 0) return HIPPO_ERR_BAD_SHAPE;
+  if (kv->stride_n > (1ll << 24)) return HIPPO_ERR_BAD_SHAPE;   // row offsets inside a tile stay 32-bit
   if (kv->batch > 65535 || kv->n_kv_heads > 65535) return HIPPO_ERR_BAD_SHAPE;
   const int per16 = 16 / elem_bytes(kv->dtype);
   if (kv->stride_n % per16 || kv->stride_h % per16 || kv->stride_b % per16) return HIPPO_ERR_BAD_ALIGN;
