@@ -246,7 +246,7 @@ def main():
         "verify_alone_GBps": round(kv_bytes / t_verify_alone / 1e9, 1),
         "roofline": {"bound": "hbm", "achieved": round(verify_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(verify_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": "hippo_verify_attention = attn_partial_mfma + attn_combine; %d algorithmic bytes "
+                     "kernel": "hippo_verify_attention = attn_partial_grid + attn_combine; %d algorithmic bytes "
                                "(K+V of one layer) per call, duration = decode round / layers" % kv_bytes},
         "input_generation_s": round(gen_s, 1),
     }

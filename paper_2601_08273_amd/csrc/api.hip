@@ -110,7 +110,7 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   p.sb = kv->stride_b; p.sh = kv->stride_h; p.sn = kv->stride_n;
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)kv->head_dim);
   p.scale_log2 = scale * kLog2e;
-  p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks;
+  p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks; p.variant = 0;
   const hipError_t e = launch_attention(p, kv->dtype, kv->head_dim, pl.mfma, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
 }

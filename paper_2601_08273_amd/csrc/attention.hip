@@ -5,7 +5,7 @@
 // One launch streams each KV slice once for all R = G * q_len query rows that share a KV head
 // (row r = i * G + g: new token i, query head g of the group), keeping an online-softmax state
 // per row; a second small launch merges the slices.  Two partial kernels:
-//   * attn_partial_mfma  -- bf16, MFMA 16x16x32: S^T = K Q^T puts the streamed tokens on the MFMA
+//   * attn_partial_grid  -- bf16, MFMA 16x16x32: S^T = K Q^T puts the streamed tokens on the MFMA
 //     M axis, so the score tile comes out in exactly the register layout the PV product
 //     O^T = V^T P^T needs for its B operand; only V goes through a transposing LDS read.
 //   * attn_partial_valu  -- fp32 or bf16 inputs, fp32 vector ALU; used for fp32 caches.
@@ -15,12 +15,19 @@
 // shipped library).  Lane 0 of every wave stores the shader clock at numbered points.
 #ifdef HIPPO_TRACE
 __device__ long long* g_hippo_trace;
-#define HIPPO_TP(i_)                                                                              \
-  if ((threadIdx.x & 63) == 0)                                                                    \
-    g_hippo_trace[((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + \
-                   (threadIdx.x >> 6)) * 16 + (i_)] = (long long)__builtin_readcyclecounter();
+#define HIPPO_TP_DECL long long tp_[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+#define HIPPO_TP(i_) tp_[i_] = (long long)__builtin_readcyclecounter();
+#define HIPPO_TP_FLUSH                                                                            \
+  if ((threadIdx.x & 63) == 0) {                                                                  \
+    long long* dst_ = g_hippo_trace +                                                             \
+        ((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * (blockDim.x >> 6) + \
+         (threadIdx.x >> 6)) * 16;                                                                \
+    for (int q_ = 0; q_ < 9; ++q_) dst_[q_] = tp_[q_];                                            \
+  }
 #else
+#define HIPPO_TP_DECL
 #define HIPPO_TP(i_)
+#define HIPPO_TP_FLUSH
 #endif
 
 namespace hippo {
@@ -163,51 +170,17 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
 }
 
 // =================================================================================================
-// MFMA partial kernel (bf16)
+// MFMA partial kernel (bf16): helpers
 // =================================================================================================
-// Work decomposition: grid (S, H_kv, B * n_chunks); a block of 4 waves owns one KV slice and up to
-// RB*16 query rows.  The slice is cut into 32-token tiles dealt round-robin to the waves; every
-// wave runs its own online softmax over its tiles (no block barrier while streaming) and the four
-// states are merged through LDS at the end.
-//
-// Data path: K/V tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no registers in
-// between) into a private two-stage ring per wave, so a wave always has the next tile in flight
-// while it works on the current one and the whole slice of a short context is requested at once.
-// The DMA is issued from inline assembly with hand-placed vmcnt waits: the compiler would
-// otherwise wait for every outstanding transfer before each LDS read.  A lane's 16 bytes land at
-// (wave-uniform base) + lane*16, so a tile is stored row-major and unpadded; bank conflicts are
-// avoided by fetching, for physical 16-byte chunk c of row r, logical chunk c ^ swz(r).
-//
-// Register layouts (lane = j + 16*g, j = lane%16, g = lane/16), v_mfma_f32_16x16x32_bf16:
-//   A operand: row j,  8 contraction elements of group g      B operand: column j, same 8 elements
-//   D result : column j, rows 4g..4g+3
-// S^T = K Q^T  -> D[token][qrow]: lane (qrow j, g) holds tokens 4g..4g+3 of a 16-token block.
-// O^T = V^T P^T -> B operand wants, for column (qrow) j and group g, 8 contraction (token) values:
-//   the two S^T blocks of a 32-token tile give exactly 8 per lane, so contraction slot 8g+e is
-//   token (e/4)*16 + 4g + e%4.  The matching V^T operand (row = head-dim element j, the same 8
-//   tokens) comes from ds_read_b64_tr_b16, which hands lane j of a 16-lane group the j-th column
-//   of a 4 x 16 block whose rows the lanes address 4 elements at a time.
-// The contraction order of QK^T is likewise free: slot (ks, g, e) reads head-dim element
-// (g*KS + ks)*8 + e of both K and Q, which makes each lane's K reads one contiguous run.
-constexpr int kMfmaTile = 32;
-constexpr int kStages = 2;            // per-wave ring depth
-constexpr float kRescaleGap = 8.f;    // log2 units
+constexpr int kMfmaTile = 32;         // tokens per tile the host-side split heuristic counts in
+constexpr float kRescaleGap = 8.f;    // log2 units, see the lazy rescale in the kernel
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-template <int D>
-struct MfmaSmem {
-  static constexpr int kRowBytes = D * 2;                      // unpadded, swizzled rows
-  static constexpr int kTileBytes = kMfmaTile * kRowBytes;     // one K or V tile
-  static constexpr int kStageBytes = 2 * kTileBytes;           // K tile then V tile
-  static constexpr int q_bytes(int rb) { return rb * 16 * kRowBytes; }
-  static constexpr int stat_bytes(int rb) { return 2 * 4 * rb * 16 * 4; }   // m and l of 4 waves
-  static constexpr int ring_bytes() { return 4 * kStages * kStageBytes; }
-  static constexpr int total(int rb) { return q_bytes(rb) + stat_bytes(rb) + ring_bytes(); }
-};
-
-// 16 bytes per lane from global memory straight into LDS at lds_addr + lane*16 (lds_addr uniform)
+// 16 bytes per lane from global memory straight into LDS at lds_addr + lane*16 (lds_addr uniform).
+// Issued from inline assembly with hand-placed vmcnt waits: the compiler would otherwise wait for
+// every outstanding transfer before each LDS read.
 __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
                : "memory");
@@ -217,285 +190,312 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D, int RB>
-__global__ __launch_bounds__(256, 2) void attn_partial_mfma(AttnParams p) {
-  using SM = MfmaSmem<D>;
-  constexpr int KS = D / 32;        // MFMA steps of QK^T
-  constexpr int DB = D / 16;        // 16-row blocks of O^T
+template <int N>
+struct WaitLadder {   // s_waitcnt vmcnt(step * later) for a run-time, wave-uniform `later` in [0, N]
+  template <int STEP>
+  static __device__ __forceinline__ void run(int later) {
+    if (later >= N) wait_vmcnt<(STEP * N > 63 ? 63 : STEP * N)>();
+    else WaitLadder<N - 1>::template run<STEP>(later);
+  }
+};
+template <>
+struct WaitLadder<0> {
+  template <int STEP>
+  static __device__ __forceinline__ void run(int) { wait_vmcnt<0>(); }
+};
+
+// =================================================================================================
+// MFMA partial kernel (bf16): query-row blocks x token groups
+// =================================================================================================
+// Grid (S, H_kv, B * n_chunks): a block owns one KV slice and up to RB*16 query rows, and has
+// RB * TG waves.  Wave (rb, tg) owns query rows 16*rb..16*rb+15 and, of every "super-tile" of TG
+// consecutive TT-token tiles, tile number tg.  A wave's state is one 16-row accumulator (32
+// registers at d = 128), so 12-16 waves fit on a compute unit and hide each other's MFMA / LDS /
+// exp latencies; at the end the TG states of a row block meet in LDS and wave (rb, tg) reduces and
+// stores head-dim blocks tg, tg + TG, ...
+//
+// Data path: K/V tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no registers in
+// between) into one ring of NST super-tiles shared by the block; the first ISSUERS waves issue the
+// transfers.  One block barrier per super-tile says both "it has landed" (every issuer waited for
+// its own transfers first) and "everyone is done with the previous one" (whose stage is refilled
+// right away).  A lane's 16 bytes land at (wave-uniform base) + lane*16, so a tile is stored
+// row-major and unpadded; bank conflicts are avoided by fetching, for physical 16-byte chunk c of
+// row r, logical chunk c ^ swz(r).
+//
+// Register layouts (lane = j + 16*g, j = lane%16, g = lane/16), v_mfma_f32_16x16x32_bf16:
+//   A operand: row j,  8 contraction elements of group g      B operand: column j, same 8 elements
+//   D result : column j, rows 4g..4g+3
+// S^T = K Q^T  -> D[token][qrow]: lane (qrow j, g) holds tokens 4g..4g+3 of a 16-token block, which
+//   is exactly what the B operand of O^T = V^T P^T wants (contraction slot 4g+e = token 4g+e; with
+//   32-token tiles the second block supplies slots 4..7 of each lane).  The matching V^T operand
+//   (row = head-dim element j, the same tokens) comes from ds_read_b64_tr_b16, which hands lane j
+//   of a 16-lane group the j-th column of a 4 x 16 block whose rows the lanes address 4 elements at
+//   a time.  The contraction order of QK^T is likewise free: slot (ks, g, e) reads head-dim element
+//   (g*KS + ks)*8 + e of both K and Q, which makes each lane's K reads one contiguous run.
+template <int D, int TG, int TT, int NST>
+struct GridSmem {
+  static constexpr int kRowBytes = D * 2;
+  static constexpr int kTileBytes = TT * kRowBytes;
+  static constexpr int kSuperBytes = TG * 2 * kTileBytes;      // TG x (K tile, V tile)
+  static constexpr int q_bytes(int rb) { return rb * 16 * kRowBytes; }
+  static constexpr int stat_bytes(int rb) { return 2 * TG * rb * 16 * 4; }
+  static constexpr int xbuf_bytes(int rb) { return rb * TG * (D / 16) * 1024; }   // merge staging
+  static constexpr int ring_bytes(int rb) {
+    return NST * kSuperBytes > xbuf_bytes(rb) ? NST * kSuperBytes : xbuf_bytes(rb);
+  }
+  static constexpr int total(int rb) { return q_bytes(rb) + stat_bytes(rb) + ring_bytes(rb); }
+};
+
+// TT = tokens per tile (16 or 32), NST = ring stages (super-tiles resident in LDS)
+template <int D, int RB, int TG, int TT, int NST>
+__global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) {
+  using SM = GridSmem<D, TG, TT, NST>;
+  constexpr int WAVES = RB * TG;
+  constexpr int KS = D / 32;
+  constexpr int DB = D / 16;
+  constexpr int TB = TT / 16;                          // 16-token blocks per tile
   constexpr int ROWB = SM::kRowBytes;
-  constexpr int CPR = D / 8;        // 16-byte chunks per row
-  constexpr int RPI = 64 / CPR;     // rows covered by one wave-wide 16-byte transfer
-  constexpr int NLD = kMfmaTile / RPI;   // transfers per K (or V) tile
-  constexpr int RPS = 256 / ROWB;   // rows per 256 bytes of LDS (one pass over all banks)
-  constexpr int NQ = RB * 16 / RPI; // transfers for the query block
+  constexpr int CPR = D / 8;
+  constexpr int RPI = 64 / CPR;
+  constexpr int NLD = TT / RPI;                        // transfers per K (or V) tile
+  constexpr int RPS = 256 / ROWB;
+  constexpr int NQ = RB * 16 / RPI;                    // transfers for the query block
+  constexpr int XFERS = TG * 2 * NLD;                  // transfers per super-tile
+  constexpr int ISSUERS = WAVES < 8 ? (XFERS < WAVES ? XFERS : WAVES) : (XFERS < 8 ? XFERS : 8);
+  constexpr int PER = XFERS / ISSUERS;                 // transfers per issuing wave per super-tile
+  static_assert(XFERS % ISSUERS == 0 && PER * (NST - 1) <= 63, "transfer split");
+  static_assert(DB % TG == 0, "head-dim blocks must split over the token groups");
+  static_assert(TT == 16 || TT == 32, "tile size");
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Qs = smem;
-  float* stat_m = (float*)(smem + SM::q_bytes(RB));          // [4][RB*16]
-  float* stat_l = stat_m + 4 * RB * 16;                      // [4][RB*16]
+  float* stat_m = (float*)(smem + SM::q_bytes(RB));          // [TG][RB*16]
+  float* stat_l = stat_m + TG * RB * 16;
   unsigned char* ring = smem + SM::q_bytes(RB) + SM::stat_bytes(RB);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rb = wave % RB, tg = wave / RB;
   const int j = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, hk = blockIdx.y;
   const int b = blockIdx.z / p.n_chunks, chunk = blockIdx.z % p.n_chunks;
   const int r0 = chunk * (RB * 16);
 
-  unsigned char* my_ring = ring + wave * (kStages * SM::kStageBytes);
-  const unsigned my_ring_addr = (unsigned)(uintptr_t)my_ring;    // LDS byte address (uniform)
+  const unsigned ring_addr = (unsigned)(uintptr_t)ring;
   const unsigned q_addr = (unsigned)(uintptr_t)Qs;
-
   const char* kbase = (const char*)p.k + ((long long)b * p.sb + (long long)hk * p.sh) * 2;
   const char* vbase = (const char*)p.v + ((long long)b * p.sb + (long long)hk * p.sh) * 2;
   const long long row_bytes = p.sn * 2;
-
-  // transfer n of a tile covers rows n*RPI + lane/CPR; this lane fills physical chunk lane%CPR
   const int ld_row = lane / CPR, ld_pc = lane % CPR;
-  unsigned ld_off[NLD];
-#pragma unroll
-  for (int n = 0; n < NLD; ++n) {
-    const int r = n * RPI + ld_row;
-    ld_off[n] = (unsigned)(r * row_bytes + ((ld_pc ^ ((r / RPS) & (CPR - 1))) * 16));
-  }
 
-  const int n_tiles = (p.n_total + kMfmaTile - 1) / kMfmaTile;
+  const int n_tiles = (p.n_total + TT - 1) / TT;
   const int t_lo = (int)((long long)split * n_tiles / p.S);
   const int t_hi = (int)((long long)(split + 1) * n_tiles / p.S);
-  const int t_first = t_lo + wave;
-  const int n_my = (t_hi > t_first) ? (t_hi - t_first + 3) / 4 : 0;   // tiles of this wave
+  const int n_blk = t_hi - t_lo;                           // tiles of this block
+  const int n_super = (n_blk + TG - 1) / TG;
 
-  // enqueue the K (which = 0) or V (which = 1) transfers of this wave's tile number i into ring
-  // stage i % kStages
-  auto issue_half = [&](int i, int which) {
-    const long long row0 = (long long)(t_first + 4 * i) * kMfmaTile;
-    const unsigned dst = my_ring_addr + (i % kStages) * SM::kStageBytes + which * SM::kTileBytes;
-    const char* base = which ? vbase : kbase;
-    if (row0 + kMfmaTile <= p.n_total) {
-      const char* tp = base + row0 * row_bytes;
+  // issuing wave w moves transfers x = w*PER .. w*PER+PER-1 of a super-tile:
+  //   x -> tile tt = x / (2 NLD), K or V = (x / NLD) & 1, 1 KB piece n = x % NLD
+  // tiles past the block's range and rows past the cache's end re-read the block's last valid row
+  // (a cache hit), so every super-tile costs every issuer exactly PER transfers
+  const long long row_cap = ((long long)t_hi * TT < p.n_total ? (long long)t_hi * TT : p.n_total) - 1;
+  auto issue_super = [&](int si) {
+    const unsigned dst = ring_addr + (si % NST) * SM::kSuperBytes;
+    const int tile0 = t_lo + si * TG;
 #pragma unroll
-      for (int n = 0; n < NLD; ++n) dma16(tp + ld_off[n], dst + n * 1024);
-    } else {   // ragged last tile: rows past the end re-read the last valid row (masked later)
-#pragma unroll
-      for (int n = 0; n < NLD; ++n) {
-        const int r = n * RPI + ld_row;
-        long long row = row0 + r;
-        row = row < p.n_total ? row : p.n_total - 1;
-        dma16(base + row * row_bytes + ((ld_pc ^ ((r / RPS) & (CPR - 1))) * 16), dst + n * 1024);
-      }
+    for (int u = 0; u < PER; ++u) {
+      const int x = wave * PER + u;
+      const int tt = x / (2 * NLD), which = (x / NLD) & 1, n = x % NLD;
+      const int r = n * RPI + ld_row;
+      long long row = (long long)(tile0 + tt) * TT + r;
+      row = row < row_cap ? row : row_cap;
+      dma16((which ? vbase : kbase) + row * row_bytes + ((ld_pc ^ ((r / RPS) & (CPR - 1))) * 16),
+            dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
     }
   };
 
+  HIPPO_TP_DECL
   HIPPO_TP(0)
-  // ---- prologue: K of tile 0, this wave's share of the query block, V of tile 0, tile 1 -- all in
-  // flight at once.  Transfers complete in issue order, so "at most n outstanding" identifies
-  // exactly which of them have landed.
-  if (n_my > 0) issue_half(0, 0);
+  // ---- prologue: the query block, then every ring stage ----
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
-    if ((n & 3) == wave) {       // wave-uniform
+    if ((n % WAVES) == wave) {
       const int rr = n * RPI + ld_row;
       int r = r0 + rr;
-      r = r < p.R ? r : p.R - 1;                        // padding rows repeat the last real row
+      r = r < p.R ? r : p.R - 1;                          // padding rows repeat the last real row
       const int i = r / p.G, gq = r % p.G;
       const char* src = (const char*)p.q + ((((long long)b * p.q_len + i) * p.H + hk * p.G + gq) * D) * 2 +
                         ((ld_pc ^ ((rr / RPS) & (CPR - 1))) * 16);
       dma16(src, q_addr + n * 1024);
     }
   }
-  if (n_my > 0) issue_half(0, 1);
-  if (n_my > 1) { issue_half(1, 0); issue_half(1, 1); }
+  const bool issuer = wave < ISSUERS;
+  int issued = n_super < NST ? n_super : NST;              // super-tiles requested so far
+  if (issuer)
+    for (int si = 0; si < issued; ++si) issue_super(si);
 
-  int lim[RB];       // last cache row visible to this lane's query row of block rb
-  float m_run[RB], l_run[RB];
-  f32x4 acc[DB][RB];
+  const int row = r0 + rb * 16 + j;                       // this lane's query row
+  const int lim = (row < p.R) ? p.ctx_len + row / p.G : 0x7fffffff;
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 acc[DB];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int r = r0 + rb * 16 + j;
-    // padding rows see everything: they stay finite and are never stored
-    lim[rb] = (r < p.R) ? p.ctx_len + r / p.G : 0x7fffffff;
-    m_run[rb] = -INFINITY;
-    l_run[rb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db) acc[db][rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  }
+  for (int db = 0; db < DB; ++db) acc[db] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // per-lane LDS offsets of the MFMA operand reads (swizzle folded in)
-  const int swz_k = (j / RPS) & (CPR - 1);            // rows tb*16 + j
+  const int swz_k = (j / RPS) & (CPR - 1);
   unsigned k_off[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) k_off[ks] = j * ROWB + (((g * KS + ks) ^ swz_k) * 16);
-  const int v_row = 4 * g + (j >> 2);                  // + tb*16
+  const int v_row = 4 * g + (j >> 2);
   const int swz_v = (v_row / RPS) & (CPR - 1);
   unsigned v_off[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
     v_off[db] = v_row * ROWB + (((2 * db + ((j & 3) >> 1)) ^ swz_v) * 16) + (j & 1) * 8;
 
-  // wait for K of tile 0 and the query block (V of tile 0 and tile 1 may still be in flight),
-  // then publish Q
-  if (n_my > 1) wait_vmcnt<3 * NLD>(); else if (n_my == 1) wait_vmcnt<NLD>(); else wait_vmcnt<0>();
-  __syncthreads();
-  HIPPO_TP(1)
+  bf16x8 qop[KS];
   int trace_it = 0;
   (void)trace_it;
 
-  for (int i = 0; i < n_my; ++i) {
-    const bool has_next = (i + 1 < n_my);             // tile i+1 is already in flight
-    if (i > 0) { if (has_next) wait_vmcnt<3 * NLD>(); else wait_vmcnt<NLD>(); }     // K landed
-    const unsigned char* Kt = my_ring + (i % kStages) * SM::kStageBytes;
+  for (int si = 0; si < n_super; ++si) {
+    // Transfers complete in issue order, so "at most PER * (super-tiles requested after si)
+    // outstanding" means super-tile si (and Q) has landed.  Waves that issue no tile transfers
+    // only ever have their share of Q in flight.
+    if (issuer) WaitLadder<NST - 1>::template run<PER>(issued - 1 - si); else wait_vmcnt<0>();
+    __syncthreads();           // super-tile si complete in LDS; everyone is past super-tile si-1
+    if (si == 0) {
+      HIPPO_TP(1)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qop[ks] = *(const bf16x8*)(Qs + rb * 16 * ROWB + k_off[ks]);
+    }
+    if (si > 0 && issued < n_super) {                      // refill the stage just vacated
+      if (issuer) issue_super(issued);
+      ++issued;
+    }
+    const int ti = si * TG + tg;                           // this wave's tile inside the block
+    if (ti >= n_blk) continue;                             // ragged last super-tile
+
+    const unsigned char* Kt = ring + (si % NST) * SM::kSuperBytes + tg * 2 * SM::kTileBytes;
     const unsigned char* Vt = Kt + SM::kTileBytes;
-    const int n0 = (t_first + 4 * i) * kMfmaTile;
+    const int n0 = (t_lo + ti) * TT;
     if (trace_it == 0) { HIPPO_TP(2) }
 
-    // ---- S^T = K Q^T for the two 16-token blocks ----
-    f32x4 s[2][RB];
+    f32x4 s[TB];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int tb = 0; tb < TB; ++tb) s[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) s[tb][rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 kop[2];
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb) kop[tb] = *(const bf16x8*)(Kt + tb * 16 * ROWB + k_off[ks]);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        const bf16x8 qop = *(const bf16x8*)(Qs + rb * 16 * ROWB + k_off[ks]);
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-          s[tb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[tb], qop, s[tb][rb], 0, 0, 0);
+      for (int tb = 0; tb < TB; ++tb) {
+        const bf16x8 kop = *(const bf16x8*)(Kt + tb * 16 * ROWB + k_off[ks]);
+        s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[ks], s[tb], 0, 0, 0);
       }
-    }
     if (trace_it == 0) { HIPPO_TP(3) }
 
-    // ---- online softmax per query row (row = lane%16 of block rb) ----
-    // The reference m_run of a row only moves when the tile maximum exceeds it by more than
-    // kRescaleGap (log2 units): probabilities then stay below 2^kRescaleGap, well inside fp32 and
-    // bf16 range, and the accumulators are rescaled a handful of times instead of once per tile.
-    if ((n0 + kMfmaTile - 1) > p.ctx_len) {            // wave-uniform: tile touches the causal edge
+    if ((n0 + TT - 1) > p.ctx_len) {                     // tile touches the causal edge
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
+      for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if ((n0 + tb * 16 + 4 * g + e) > lim[rb]) s[tb][rb][e] = -INFINITY;
+        for (int e = 0; e < 4; ++e)
+          if ((n0 + tb * 16 + 4 * g + e) > lim) s[tb][e] = -INFINITY;
     }
-    bool grow = false;
-    float mx[RB];
+    float m8 = fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3]));
+    if (TB == 2) m8 = fmaxf(m8, fmaxf(fmaxf(s[TB - 1][0], s[TB - 1][1]), fmaxf(s[TB - 1][2], s[TB - 1][3])));
+    m8 = fmaxf(m8, __shfl_xor(m8, 16, 64));
+    m8 = fmaxf(m8, __shfl_xor(m8, 32, 64));
+    const float mx = m8 * p.scale_log2;                    // scale > 0: max commutes with it
+    // lazy rescale: the reference m_run moves only when the tile maximum exceeds it by more than
+    // kRescaleGap, so probabilities stay below 2^kRescaleGap and rescales are rare
+    const bool up = mx > m_run + kRescaleGap;              // also true for the first finite maximum
+    if (__any(up)) {
+      const float a = up ? fast_exp2(m_run - mx) : 1.f;    // m_run = -inf -> 0
+      if (up) m_run = mx;
+      l_run *= a;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      float m8 = fmaxf(fmaxf(fmaxf(s[0][rb][0], s[0][rb][1]), fmaxf(s[0][rb][2], s[0][rb][3])),
-                       fmaxf(fmaxf(s[1][rb][0], s[1][rb][1]), fmaxf(s[1][rb][2], s[1][rb][3])));
-      m8 = fmaxf(m8, __shfl_xor(m8, 16, 64));
-      m8 = fmaxf(m8, __shfl_xor(m8, 32, 64));
-      mx[rb] = m8 * p.scale_log2;                      // scale > 0: max commutes with it
-      grow |= mx[rb] > m_run[rb] + kRescaleGap;        // also true for the first finite maximum
+      for (int db = 0; db < DB; ++db) acc[db] *= a;
     }
-    if (__any(grow)) {
+    const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+    // the PV product sees P rounded to bf16; the denominator sums the same rounded values
+    __bf16 pb[TB * 4];
+    float psum = 0.f;
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        const bool up = mx[rb] > m_run[rb] + kRescaleGap;
-        const float a = up ? fast_exp2(m_run[rb] - mx[rb]) : 1.f;    // m_run = -inf -> 0
-        if (up) m_run[rb] = mx[rb];
-        l_run[rb] *= a;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) acc[db][rb] *= a;
-      }
+    for (int e = 0; e < TB * 4; ++e) {
+      pb[e] = (__bf16)fast_exp2(fmaf(s[e >> 2][e & 3], p.scale_log2, neg_m));
+      psum += (float)pb[e];
     }
-    bf16x8 pop[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const float neg_m = (m_run[rb] == -INFINITY) ? 0.f : -m_run[rb];
-      float psum = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        // the PV product sees P rounded to bf16; sum the rounded value so numerator and
-        // denominator stay consistent
-        const __bf16 pb = (__bf16)fast_exp2(fmaf(s[e >> 2][rb][e & 3], p.scale_log2, neg_m));
-        psum += (float)pb;
-        pop[rb][e] = pb;
-      }
-      l_run[rb] += psum;                               // per-lane share; the 4 groups g meet at the end
-    }
+    l_run += psum;                                         // per-lane share; groups g meet at the end
     if (trace_it == 0) { HIPPO_TP(4) }
 
-    // ---- O^T += V^T P^T ----
-    if (has_next) wait_vmcnt<2 * NLD>(); else wait_vmcnt<0>();                      // V landed
+    if (TB == 2) {
+      bf16x8 pop;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4*)(Vt + v_off[db]));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4*)(Vt + 16 * ROWB + v_off[db]));
-      const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      for (int e = 0; e < 8; ++e) pop[e] = pb[e % (TB * 4)];
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        acc[db][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop[rb], acc[db][rb], 0, 0, 0);
+      for (int db = 0; db < DB; ++db) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(Vt + v_off[db]));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(Vt + (TB - 1) * 16 * ROWB + v_off[db]));
+        const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop, acc[db], 0, 0, 0);
+      }
+    } else {
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+      bf16x4 pop4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pop4[e] = pb[e];
+      const s16x4 pop = __builtin_bit_cast(s16x4, pop4);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const s16x4 vop = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(Vt + v_off[db]));
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop, pop, acc[db], 0, 0, 0);
+      }
     }
     if (trace_it == 0) { HIPPO_TP(5) }
     ++trace_it;
-
-    // the stage is free again: every LDS read of it has returned (the MFMAs consumed them)
-    if (i + kStages < n_my) {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      issue_half(i + kStages, 0);
-      issue_half(i + kStages, 1);
-    }
   }
+  wait_vmcnt<0>();   // no transfer may still be writing LDS past this point
   HIPPO_TP(6)
 
-  // ---- merge the 4 waves: wave w reduces and stores head-dim blocks w, w+4, ... of all rows ----
-  // every wave publishes its (m, l) and its unscaled accumulators; the ring is free by then
-  // because each wave has drained its own transfers and the barrier orders the rest
-  f32x4* xbuf = (f32x4*)ring;                               // [4 waves][DB][RB][64 lanes]
-  auto xbuf_at = [&](int w, int db, int rb) { return xbuf + ((w * DB + db) * RB + rb) * 64 + lane; };
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    l_run[rb] += __shfl_xor(l_run[rb], 16, 64);
-    l_run[rb] += __shfl_xor(l_run[rb], 32, 64);
-    if (g == 0) {
-      stat_m[wave * RB * 16 + rb * 16 + j] = m_run[rb];
-      stat_l[wave * RB * 16 + rb * 16 + j] = l_run[rb];
-    }
+  // ---- merge the TG token groups of every row block ----
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (g == 0) {
+    stat_m[tg * RB * 16 + rb * 16 + j] = m_run;
+    stat_l[tg * RB * 16 + rb * 16 + j] = l_run;
   }
-  __syncthreads();   // (a) every wave is done reading its ring before anyone overwrites it
+  f32x4* xbuf = (f32x4*)ring;                              // [WAVES][DB][64 lanes]
+  __syncthreads();   // (a) every wave is done reading the ring before anyone overwrites it
   HIPPO_TP(7)
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) *xbuf_at(wave, db, rb) = acc[db][rb];
+  for (int db = 0; db < DB; ++db) xbuf[(wave * DB + db) * 64 + lane] = acc[db];
   __syncthreads();   // (b) accumulators and statistics of all waves visible
   {
+    float mw[TG], mm = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < TG; ++w) { mw[w] = stat_m[w * RB * 16 + rb * 16 + j]; mm = fmaxf(mm, mw[w]); }
+    float f[TG], ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < TG; ++w) {
+      f[w] = (mw[w] == -INFINITY) ? 0.f : fast_exp2(mw[w] - mm);
+      ll = fmaf(f[w], stat_l[w * RB * 16 + rb * 16 + j], ll);
+    }
     const long long slot = ((long long)b * p.Hkv + hk) * p.S + split;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const int r = r0 + rb * 16 + j;
-      float mw[4], mm = -INFINITY;
+    for (int dd = 0; dd < DB / TG; ++dd) {
+      const int db = tg + TG * dd;
+      f32x4 o = xbuf[((0 * RB + rb) * DB + db) * 64 + lane] * f[0];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) { mw[w] = stat_m[w * RB * 16 + rb * 16 + j]; mm = fmaxf(mm, mw[w]); }
-      float f[4], ll = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        f[w] = (mw[w] == -INFINITY) ? 0.f : fast_exp2(mw[w] - mm);
-        ll = fmaf(f[w], stat_l[w * RB * 16 + rb * 16 + j], ll);
-      }
-#pragma unroll
-      for (int dd = 0; dd < DB / 4; ++dd) {
-        const int db = wave + 4 * dd;
-        f32x4 o = *xbuf_at(0, db, rb) * f[0];
-#pragma unroll
-        for (int w = 1; w < 4; ++w) o += *xbuf_at(w, db, rb) * f[w];
-        if (r < p.R) *(f32x4*)(p.part_o + (slot * p.R + r) * D + db * 16 + 4 * g) = o;
-      }
-      if (wave == 0 && g == 0 && r < p.R) {
-        p.part_m[slot * p.R + r] = mm;
-        p.part_l[slot * p.R + r] = ll;
-      }
+      for (int w = 1; w < TG; ++w) o += xbuf[((w * RB + rb) * DB + db) * 64 + lane] * f[w];
+      if (row < p.R) *(f32x4*)(p.part_o + (slot * p.R + row) * D + db * 16 + 4 * g) = o;
+    }
+    if (tg == 0 && g == 0 && row < p.R) {
+      p.part_m[slot * p.R + row] = mm;
+      p.part_l[slot * p.R + row] = ll;
     }
   }
   HIPPO_TP(8)
+  HIPPO_TP_FLUSH
 }
 
 // =================================================================================================
@@ -577,28 +577,38 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
 // =================================================================================================
 // host launch
 // =================================================================================================
-template <int D, int RB>
-static hipError_t launch_mfma(const AttnParams& p, hipStream_t st) {
-  constexpr int smem = MfmaSmem<D>::total(RB);
+template <int D, int RB, int TG, int TT, int NST>
+static hipError_t launch_grid(const AttnParams& p, hipStream_t st) {
+  constexpr int smem = GridSmem<D, TG, TT, NST>::total(RB);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_mfma<D, RB>,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid(p.S, p.Hkv, p.B * p.n_chunks);
-  hipLaunchKernelGGL((attn_partial_mfma<D, RB>), grid, dim3(256), smem, st, p);
+  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST>), grid, dim3(RB * TG * 64), smem, st, p);
   return hipGetLastError();
+}
+
+// Short slices (a block owns only a handful of tiles, as at 16K context on 256 compute units) use
+// 16-token tiles and a three-stage ring: the first data then arrives early enough for the math to
+// overlap the rest of the stream.  Long slices use 32-token tiles, which halve the barrier count.
+template <int D, int RB>
+static hipError_t launch_grid_rb(const AttnParams& p, hipStream_t st) {
+  const int tiles32_per_block = ((p.n_total + 31) / 32) / (p.S > 0 ? p.S : 1);
+  const bool small_tiles = p.variant == 1 || (p.variant != 2 && tiles32_per_block < 24);
+  return small_tiles ? launch_grid<D, RB, 4, 16, 3>(p, st) : launch_grid<D, RB, 4, 32, 2>(p, st);
 }
 
 template <int D>
 static hipError_t launch_mfma_d(const AttnParams& p, hipStream_t st) {
   switch (p.row_chunk / 16) {
-    case 1: return launch_mfma<D, 1>(p, st);
-    case 2: return launch_mfma<D, 2>(p, st);
-    case 3: return launch_mfma<D, 3>(p, st);
-    default: return launch_mfma<D, 4>(p, st);
+    case 1: return launch_grid_rb<D, 1>(p, st);
+    case 2: return launch_grid_rb<D, 2>(p, st);
+    case 3: return launch_grid_rb<D, 3>(p, st);
+    default: return launch_grid_rb<D, 4>(p, st);
   }
 }
 

@@ -83,6 +83,7 @@ struct AttnParams {
   int S;                  // number of KV splits
   int row_chunk;          // query rows handled by one block
   int n_chunks;           // ceil(R / row_chunk)
+  int variant;            // tile-size override for tuning runs: 0 = heuristic, 1 = 16-token, 2 = 32-token
 };
 
 // Launchers, one per translation unit.  All return a hipError_t from hipGetLastError().
