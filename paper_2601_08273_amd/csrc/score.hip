@@ -109,129 +109,156 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
 }
 
 // =================================================================================================
-// s_attn, MFMA version (bf16).  Block = 4 waves x 64 tokens; each wave keeps its 64 keys as MFMA A
+// s_attn, MFMA version (bf16).  Block = 8 waves x 32 tokens; each wave keeps its 32 keys as MFMA A
 // operands in registers for the whole sweep over the query rows, which are staged through LDS in
 // chunks of 64 rows.  Z^T = K Q^T: lane (row j, group g) holds tokens tb*16 + 4g + e.
 // =================================================================================================
-constexpr int kSaMfmaTile = 256;
+constexpr int kSaMfmaTile = 256;      // tokens per block
+constexpr int kSaWaves = 8;           // waves per block, 32 tokens each: two waves per SIMD overlap MFMA and exp
 
 template <int D, int PASS>
-__global__ __launch_bounds__(256) void sattn_mfma(ScoreParams p) {
+__global__ __launch_bounds__(kSaWaves * 64) void sattn_mfma(ScoreParams p) {
+  constexpr int NW = kSaWaves, NT = NW * 64;
+  constexpr int TPW = kSaMfmaTile / NW;   // tokens per wave
+  constexpr int TBW = TPW / 16;           // 16-token blocks per wave
   constexpr int KS = D / 32;
   constexpr int ROWB = D * 2 + 16;
   constexpr int CPR = D / 8;
   constexpr int RCH = 64;               // query rows per LDS chunk
   __shared__ __align__(16) unsigned char Qs[RCH * ROWB];
   __shared__ float lse_s[RCH];
-  __shared__ float wm_s[4][RCH];
-  __shared__ float wl_s[4][RCH];
+  constexpr int RDEF = 512;             // pass 1 merges the waves' row statistics every RDEF rows
+  __shared__ float wm_s[PASS == 1 ? NW : 1][PASS == 1 ? RDEF : 1];
+  __shared__ float wl_s[PASS == 1 ? NW : 1][PASS == 1 ? RDEF : 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
   const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
-  const int n0 = tile * kSaMfmaTile + wave * 64;     // first token of this wave
+  const int n0 = tile * kSaMfmaTile + wave * TPW;    // first token of this wave
   const int Rs = p.L * p.G;
   const float scale_log2 = rsqrtf((float)D) * kLog2e;
 
   const uint16_t* kbase = (const uint16_t*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
                           (long long)p.vis_off * p.sn;
   // this wave's keys as A operands: token tb*16 + j, head-dim elements (g*KS + ks)*8 .. +8
-  bf16x8 kop[4][KS];
+  bf16x8 kop[TBW][KS];
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb) {
+  for (int tb = 0; tb < TBW; ++tb) {
     int n = n0 + tb * 16 + j;
     n = n < p.Nv ? n : p.Nv - 1;                     // in bounds; masked below
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       kop[tb][ks] = *(const bf16x8*)(kbase + (long long)n * p.sn + (g * KS + ks) * 8);
   }
-  bool tok_ok[4][4];
+  bool tok_ok[TBW][4];
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
+  for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
     for (int e = 0; e < 4; ++e) tok_ok[tb][e] = (n0 + tb * 16 + 4 * g + e) < p.Nv;
   const bool wave_has_tokens = n0 < p.Nv;
+  const bool wave_full = n0 + TPW <= p.Nv;
 
-  float col[4][4];
+  float col[TBW][4];
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
+  for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
     for (int e = 0; e < 4; ++e) col[tb][e] = 0.f;
 
-  for (int r0 = 0; r0 < Rs; r0 += RCH) {
-    __syncthreads();
-    for (int e = tid; e < RCH * CPR; e += 256) {
+  // query rows are staged 64 at a time; the next chunk is fetched into registers while the
+  // current one is being multiplied, so the trip to memory hides behind the MFMAs
+  constexpr int QPT = (RCH * CPR + NT - 1) / NT;   // 16-byte pieces per thread per chunk
+  u32x4 qreg[QPT];
+  float lse_reg = INFINITY;
+  auto fetch_chunk = [&](int r0) {
+#pragma unroll
+    for (int u = 0; u < QPT; ++u) {
+      const int e = tid + NT * u;
       const int rr = e / CPR, ch = e % CPR, r = r0 + rr;
-      u32x4 val = (u32x4){0u, 0u, 0u, 0u};
-      if (r < Rs) {
+      qreg[u] = (u32x4){0u, 0u, 0u, 0u};
+      if (e < RCH * CPR && r < Rs) {
         const int i = r / p.G, gq = r % p.G;
-        val = *(const u32x4*)((const uint16_t*)p.q_txt +
-                              (((long long)b * p.L + i) * p.H + hk * p.G + gq) * D + ch * 8);
+        qreg[u] = *(const u32x4*)((const uint16_t*)p.q_txt +
+                                  (((long long)b * p.L + i) * p.H + hk * p.G + gq) * D + ch * 8);
       }
-      *(u32x4*)(Qs + rr * ROWB + ch * 16) = val;
     }
     if (PASS == 2 && tid < RCH) {
       const int r = r0 + tid;
-      float v = INFINITY;
-      if (r < Rs) v = p.row_lse[((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G];
-      lse_s[tid] = v;
+      lse_reg = INFINITY;                     // padding rows contribute exp2(-inf) = 0
+      if (r < Rs) lse_reg = p.row_lse[((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G];
     }
+  };
+  fetch_chunk(0);
+  for (int r0 = 0; r0 < Rs; r0 += RCH) {
+    __syncthreads();                          // everyone is done with the previous chunk
+#pragma unroll
+    for (int u = 0; u < QPT; ++u) {
+      const int e = tid + NT * u;
+      if (e < RCH * CPR) *(u32x4*)(Qs + (e / CPR) * ROWB + (e % CPR) * 16) = qreg[u];
+    }
+    if (PASS == 2 && tid < RCH) lse_s[tid] = lse_reg;
     __syncthreads();
+    if (r0 + RCH < Rs) fetch_chunk(r0 + RCH);
 
 #pragma unroll
     for (int rb = 0; rb < RCH / 16; ++rb) {
-      f32x4 z[4];
+      f32x4 z[TBW];
 #pragma unroll
-      for (int tb = 0; tb < 4; ++tb) z[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int tb = 0; tb < TBW; ++tb) z[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 qop = *(const bf16x8*)(Qs + (rb * 16 + j) * ROWB + (g * KS + ks) * 16);
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+        for (int tb = 0; tb < TBW; ++tb)
           z[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[tb][ks], qop, z[tb], 0, 0, 0);
       }
       if (PASS == 1) {
-        float mx = -INFINITY;
+        if (!wave_full) {                       // wave-uniform: only the ragged last wave masks
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+          for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            z[tb][e] = tok_ok[tb][e] ? z[tb][e] * scale_log2 : -INFINITY;
-            mx = fmaxf(mx, z[tb][e]);
-          }
+            for (int e = 0; e < 4; ++e)
+              if (!tok_ok[tb][e]) z[tb][e] = -INFINITY;
+        }
+        float mx = -INFINITY;                   // the scale is positive: take the max of the raw logits
+#pragma unroll
+        for (int tb = 0; tb < TBW; ++tb)
+          mx = fmaxf(mx, fmaxf(fmaxf(z[tb][0], z[tb][1]), fmaxf(z[tb][2], z[tb][3])));
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+        mx *= scale_log2;
+        const float neg_m = (mx == -INFINITY) ? 0.f : -mx;
         float ps = 0.f;
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+        for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ps += fast_exp2(z[tb][e] - m_safe);
+          for (int e = 0; e < 4; ++e) ps += fast_exp2(fmaf(z[tb][e], scale_log2, neg_m));
         ps += __shfl_xor(ps, 16, 64);
         ps += __shfl_xor(ps, 32, 64);
         if (g == 0) {
-          wm_s[wave][rb * 16 + j] = mx;
-          wl_s[wave][rb * 16 + j] = ps;
+          wm_s[wave][(r0 % RDEF) + rb * 16 + j] = mx;
+          wl_s[wave][(r0 % RDEF) + rb * 16 + j] = ps;
         }
       } else {
         const float lse = lse_s[rb * 16 + j];
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+        for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) col[tb][e] += fast_exp2(z[tb][e] * scale_log2 - lse);
+          for (int e = 0; e < 4; ++e) col[tb][e] += fast_exp2(fmaf(z[tb][e], scale_log2, -lse));
       }
     }
-    if (PASS == 1) {
+    if (PASS == 1 && (((r0 + RCH) % RDEF) == 0 || r0 + RCH >= Rs)) {
+      // merge the waves' (max, sum) of the rows gathered since the last merge and write them out
       __syncthreads();
-      if (tid < RCH && (r0 + tid) < Rs) {
+      const int base = r0 - (r0 % RDEF);
+      for (int rr = tid; rr < RDEF && base + rr < Rs && base + rr < r0 + RCH; rr += NT) {
         float mm = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) mm = fmaxf(mm, wm_s[w][tid]);
+        for (int w = 0; w < NW; ++w) mm = fmaxf(mm, wm_s[w][rr]);
         float ll = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-          ll += (wm_s[w][tid] == -INFINITY) ? 0.f : wl_s[w][tid] * fast_exp2(wm_s[w][tid] - mm);
-        const int r = r0 + tid;
+        for (int w = 0; w < NW; ++w)
+          ll += (wm_s[w][rr] == -INFINITY) ? 0.f : wl_s[w][rr] * fast_exp2(wm_s[w][rr] - mm);
+        const int r = base + rr;
         const long long row = ((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G;
         p.row_m[row * p.n_tile + tile] = mm;
         p.row_l[row * p.n_tile + tile] = ll;
@@ -241,7 +268,7 @@ __global__ __launch_bounds__(256) void sattn_mfma(ScoreParams p) {
   if (PASS == 2 && wave_has_tokens) {
     // sum the 16 rows held by the lanes of each group g
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
+    for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         float v = col[tb][e];
@@ -253,18 +280,21 @@ __global__ __launch_bounds__(256) void sattn_mfma(ScoreParams p) {
   }
 }
 
-// merge the per-tile row statistics: lse2 = m* + log2(sum_t l_t 2^(m_t - m*))
+// merge the per-tile row statistics: lse2 = m* + log2(sum_t l_t 2^(m_t - m*)); one wave per row
 __global__ __launch_bounds__(256) void sattn_row_lse(ScoreParams p) {
-  const long long row = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   if (row >= (long long)p.B * p.H * p.L) return;
   float mm = -INFINITY;
-  for (int t = 0; t < p.n_tile; ++t) mm = fmaxf(mm, p.row_m[row * p.n_tile + t]);
+  for (int t = lane; t < p.n_tile; t += 64) mm = fmaxf(mm, p.row_m[row * p.n_tile + t]);
+  mm = wave_max(mm);
   float ll = 0.f;
-  for (int t = 0; t < p.n_tile; ++t) {
+  for (int t = lane; t < p.n_tile; t += 64) {
     const float m = p.row_m[row * p.n_tile + t];
     if (m != -INFINITY) ll += p.row_l[row * p.n_tile + t] * fast_exp2(m - mm);
   }
-  p.row_lse[row] = mm + __log2f(ll);
+  ll = wave_sum(ll);
+  if (lane == 0) p.row_lse[row] = mm + __log2f(ll);
 }
 
 // s_attn[b,j] = sum_hk col_part / (H L)  (+ running layer sum)
@@ -418,6 +448,267 @@ __global__ __launch_bounds__(256) void emb_scores(ScoreParams p) {
 }
 
 // =================================================================================================
+// s_temp and s_spa on MFMA (bf16): one block per (crop, frame, batch element), RBC*16 >= crop size.
+// The crop's Gram matrix E E^T and the temporal products (E_f E_{f-1}^T, E_{f-1} E_{f-1}^T and the
+// same for f+1, of which only the diagonals are used) are 16x16 output blocks of one and the same
+// operand: a lane's A operand for row block rb -- token rb*16 + lane%16, 8 consecutive channels --
+// is also the B operand for that block of columns, and it is read straight from global memory
+// (16 bytes per lane; the 4 lane groups of a token cover 64 contiguous bytes).  The 16x16 blocks
+// are dealt to the 4 waves, each sweeping all channels for its blocks, so nothing is reduced
+// across waves; the finished Gram goes to LDS and one thread per token finishes Eq. 4 and Eq. 6.
+// =================================================================================================
+template <int RBC>
+__global__ __launch_bounds__(256) void emb_scores_mfma(ScoreParams p) {
+  constexpr int MP = RBC * 16;
+  constexpr int N_GRAM = RBC * (RBC + 1) / 2;      // upper-triangle blocks
+  constexpr int N_ITEMS = N_GRAM + 4 * RBC;        // + (prev dot, prev norm, next dot, next norm) x RBC
+  __shared__ float G[MP][MP + 1];
+  __shared__ float tdot[4][MP];                     // v.prev, |prev|^2, v.next, |next|^2
+  __shared__ int tok_s[MP];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, g = lane >> 4;
+  const int ncx = (p.gw + p.cw - 1) / p.cw;
+  const int cy = blockIdx.x / ncx, cx = blockIdx.x % ncx;
+  const int f = blockIdx.y, b = blockIdx.z;
+  const int y0 = cy * p.ch, x0 = cx * p.cw;
+  const int mh = min(p.ch, p.gh - y0), mw = min(p.cw, p.gw - x0);
+  const int M = mh * mw;
+  if (tid < MP) {
+    const int t = tid < M ? tid : M - 1;            // padding slots repeat the last token
+    tok_s[tid] = f * p.P + (y0 + t / mw) * p.gw + x0 + t % mw;
+  }
+  const bool has_prev = f > 0, has_next = f + 1 < p.F;
+  const int de = p.emb ? p.emb_dim : p.Hkv * p.D;
+  const int n_ks = (de + 31) / 32;
+  __syncthreads();
+
+  // operand of frame offset `df` (-1, 0, +1), row block rbk, channel step ks
+  auto operand = [&](int df, int rbk, int ks) -> bf16x8 {
+    const int c = ks * 32 + g * 8;
+    if (c >= de) return (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+    const long long tokn = tok_s[rbk * 16 + j] + (long long)df * p.P;
+    const uint16_t* src;
+    if (p.emb) {
+      src = (const uint16_t*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok + c;
+    } else {
+      const int hk = c / p.D, cc = c % p.D;
+      src = (const uint16_t*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
+            (p.vis_off + tokn) * p.sn + cc;
+    }
+    return *(const bf16x8*)src;
+  };
+
+  for (int item = wave; item < N_ITEMS; item += 4) {          // wave-uniform
+    int da, db_, ra, rbk;                                      // frame offsets and row blocks of A and B
+    int kind = -1;                                             // -1 Gram, 0..3 temporal quantity
+    if (item < N_GRAM) {
+      int bi = 0, rem = item;
+      while (rem >= RBC - bi) { rem -= RBC - bi; ++bi; }
+      ra = bi; rbk = bi + rem; da = 0; db_ = 0;
+    } else {
+      const int t = item - N_GRAM;
+      kind = t / RBC;
+      ra = rbk = t % RBC;
+      const int dn = kind < 2 ? -1 : 1;
+      if ((dn < 0 && !has_prev) || (dn > 0 && !has_next)) continue;
+      da = (kind & 1) ? dn : 0;                                // norm: neighbour with itself
+      db_ = dn;
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const bool same = (da == db_) && (ra == rbk);              // diagonal block: one operand serves both
+    for (int ks0 = 0; ks0 < n_ks; ks0 += 8) {                  // 8 channel steps of loads in flight
+      bf16x8 a[8], bb[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] = operand(da, ra, ks0 + u);
+      if (same) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) bb[u] = a[u];
+      } else {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) bb[u] = operand(db_, rbk, ks0 + u);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], bb[u], acc, 0, 0, 0);
+    }
+    // D[i][j']: this lane holds column j' = j, rows i = 4g..4g+3
+    if (kind < 0) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        G[ra * 16 + 4 * g + e][rbk * 16 + j] = acc[e];
+        G[rbk * 16 + j][ra * 16 + 4 * g + e] = acc[e];
+      }
+    } else if ((j >> 2) == g) {
+      tdot[kind][ra * 16 + j] = acc[j & 3];
+    }
+  }
+  __syncthreads();
+
+  if (tid < M) {
+    const int a = tid;
+    const float na = G[a][a];
+    float mu = 0.f;
+    for (int c2 = 0; c2 < M; ++c2) {
+      const float nb = G[c2][c2];
+      mu += (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+    }
+    mu /= (float)M;
+    float var = 0.f;
+    for (int c2 = 0; c2 < M; ++c2) {
+      const float nb = G[c2][c2];
+      const float cs = (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      var = fmaf(cs - mu, cs - mu, var);
+    }
+    const long long o = (long long)b * p.Nv + tok_s[a];
+    p.s_spa[o] = var / (float)M;
+    float sum = 0.f;
+    int cnt = 0;
+    if (has_prev) {
+      const float nb = tdot[1][a];
+      sum += (na > 0.f && nb > 0.f) ? tdot[0][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      ++cnt;
+    }
+    if (has_next) {
+      const float nb = tdot[3][a];
+      sum += (na > 0.f && nb > 0.f) ? tdot[2][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      ++cnt;
+    }
+    p.s_temp[o] = 1.f - (cnt ? sum / (float)cnt : 0.f);
+  }
+}
+
+// =================================================================================================
+// s_temp and s_spa on MFMA, crops of at most 32 tokens (the paper's 5 x 5): channel-split variant.
+// Same products as emb_scores_mfma, but here the 4 waves split the CHANNELS (wave w takes channel
+// steps w, w+4, ...), so every operand is fetched from memory exactly once per block; the waves'
+// partial 16x16 blocks are summed through LDS.
+// =================================================================================================
+__global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
+  constexpr int MP = 32;
+  constexpr int NBLK = 11;   // Gram (0,0) (0,1) (1,1); then for prev and next: dot rb0, dot rb1, norm rb0, norm rb1
+  __shared__ f32x4 red[4][NBLK][64];
+  __shared__ float G[MP][MP + 1];
+  __shared__ float tdot[4][MP];
+  __shared__ int tok_s[MP];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, g = lane >> 4;
+  const int ncx = (p.gw + p.cw - 1) / p.cw;
+  const int cy = blockIdx.x / ncx, cx = blockIdx.x % ncx;
+  const int f = blockIdx.y, b = blockIdx.z;
+  const int y0 = cy * p.ch, x0 = cx * p.cw;
+  const int mh = min(p.ch, p.gh - y0), mw = min(p.cw, p.gw - x0);
+  const int M = mh * mw;
+  if (tid < MP) {
+    const int t = tid < M ? tid : M - 1;            // padding slots repeat the last token
+    tok_s[tid] = f * p.P + (y0 + t / mw) * p.gw + x0 + t % mw;
+  }
+  const bool has_prev = f > 0, has_next = f + 1 < p.F;
+  const int de = p.emb ? p.emb_dim : p.Hkv * p.D;
+  const int n_ks = (de + 31) / 32;
+  __syncthreads();
+
+  // frames without a neighbour re-read the frame itself (finite data, result unused)
+  const int dprev = has_prev ? -1 : 0, dnext = has_next ? 1 : 0;
+  auto operand = [&](int df, int rbk, int ks) -> bf16x8 {
+    const int c = ks * 32 + g * 8;
+    if (ks >= n_ks || c >= de) return (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+    const long long tokn = tok_s[rbk * 16 + j] + (long long)df * p.P;
+    const uint16_t* src;
+    if (p.emb) {
+      src = (const uint16_t*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok + c;
+    } else {
+      const int hk = c / p.D, cc = c % p.D;
+      src = (const uint16_t*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
+            (p.vis_off + tokn) * p.sn + cc;
+    }
+    return *(const bf16x8*)src;
+  };
+
+  f32x4 acc[NBLK];
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int ks0 = wave; ks0 < n_ks; ks0 += 16) {       // 4 channel steps of this wave per round
+    bf16x8 cur[4][2], prv[4][2], nxt[4][2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int rbk = 0; rbk < 2; ++rbk) {
+        cur[u][rbk] = operand(0, rbk, ks0 + 4 * u);
+        prv[u][rbk] = operand(dprev, rbk, ks0 + 4 * u);
+        nxt[u][rbk] = operand(dnext, rbk, ks0 + 4 * u);
+      }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][0], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][1], acc[1], 0, 0, 0);
+      acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][1], cur[u][1], acc[2], 0, 0, 0);
+#pragma unroll
+      for (int rbk = 0; rbk < 2; ++rbk) {
+        acc[3 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][rbk], prv[u][rbk], acc[3 + rbk], 0, 0, 0);
+        acc[5 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(prv[u][rbk], prv[u][rbk], acc[5 + rbk], 0, 0, 0);
+        acc[7 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][rbk], nxt[u][rbk], acc[7 + rbk], 0, 0, 0);
+        acc[9 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(nxt[u][rbk], nxt[u][rbk], acc[9 + rbk], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) red[wave][i][lane] = acc[i];
+  __syncthreads();
+  // sum the 4 waves; thread (blk = tid/64 + 4x, lane) finishes block blk
+  for (int blk = wave; blk < NBLK; blk += 4) {
+    const f32x4 v = red[0][blk][lane] + red[1][blk][lane] + red[2][blk][lane] + red[3][blk][lane];
+    // D[i][j']: this lane holds column j' = j, rows i = 4g..4g+3
+    if (blk < 3) {
+      const int ra = blk == 2 ? 1 : 0, rbk = blk == 0 ? 0 : 1;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        G[ra * 16 + 4 * g + e][rbk * 16 + j] = v[e];
+        G[rbk * 16 + j][ra * 16 + 4 * g + e] = v[e];
+      }
+    } else if ((j >> 2) == g) {
+      const int t = blk - 3;               // 0,1 prev dot; 2,3 prev norm; 4,5 next dot; 6,7 next norm
+      tdot[t >> 1][(t & 1) * 16 + j] = v[j & 3];
+    }
+  }
+  __syncthreads();
+
+  if (tid < M) {
+    const int a = tid;
+    const float na = G[a][a];
+    float mu = 0.f;
+    for (int c2 = 0; c2 < M; ++c2) {
+      const float nb = G[c2][c2];
+      mu += (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+    }
+    mu /= (float)M;
+    float var = 0.f;
+    for (int c2 = 0; c2 < M; ++c2) {
+      const float nb = G[c2][c2];
+      const float cs = (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      var = fmaf(cs - mu, cs - mu, var);
+    }
+    const long long o = (long long)b * p.Nv + tok_s[a];
+    p.s_spa[o] = var / (float)M;
+    float sum = 0.f;
+    int cnt = 0;
+    if (has_prev) {
+      const float nb = tdot[1][a];
+      sum += (na > 0.f && nb > 0.f) ? tdot[0][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      ++cnt;
+    }
+    if (has_next) {
+      const float nb = tdot[3][a];
+      sum += (na > 0.f && nb > 0.f) ? tdot[2][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      ++cnt;
+    }
+    p.s_temp[o] = 1.f - (cnt ? sum / (float)cnt : 0.f);
+  }
+}
+
+// =================================================================================================
 // Eq. 7: per-frame z-scores, summed over the enabled terms.  One block per (frame, batch element).
 // =================================================================================================
 __device__ __forceinline__ float block_sum_256(float v, float* red) {
@@ -432,6 +723,22 @@ __global__ __launch_bounds__(256) void fuse_scores(ScoreParams p) {
   __shared__ float red[4];
   const int f = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const long long base = (long long)b * p.Nv + (long long)f * p.P;
+  if (p.flags & HIPPO_SCORE_ATTN) {
+    // s_attn[b,j] = sum_hk col_part / (H L) (+ the running layer sum), for this frame's tokens
+    for (int i = tid; i < p.P; i += 256) {
+      const long long e = base + i;
+      const int jj = f * p.P + i;
+      float a = 0.f;
+      for (int hk = 0; hk < p.Hkv; ++hk) a += p.col_part[((long long)b * p.Hkv + hk) * p.Nv + jj];
+      a /= (float)p.H * (float)p.L;
+      if (p.attn_mass_inout != nullptr) {
+        a += p.attn_mass_inout[e];
+        p.attn_mass_inout[e] = a;
+      }
+      p.s_attn[e] = a;
+    }
+    __syncthreads();   // the block re-reads its own s_attn values below
+  }
   const float* terms[3] = {p.s_attn, p.s_temp, p.s_spa};
   float mu[3], inv_sigma[3];
 #pragma unroll
@@ -473,7 +780,7 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
   dim3 grid(p.n_tile, p.Hkv, p.B);
   hipLaunchKernelGGL((sattn_valu<T, D, 1>), grid, dim3(256), 0, st, p);
   const long long rows = (long long)p.B * p.H * p.L;
-  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p);
   hipLaunchKernelGGL((sattn_valu<T, D, 2>), grid, dim3(256), 0, st, p);
   return hipGetLastError();
 }
@@ -481,10 +788,10 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
 template <int D>
 static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st) {
   dim3 grid(p.n_tile, p.Hkv, p.B);
-  hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(256), 0, st, p);
+  hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(kSaWaves * 64), 0, st, p);
   const long long rows = (long long)p.B * p.H * p.L;
-  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, p);
-  hipLaunchKernelGGL((sattn_mfma<D, 2>), grid, dim3(256), 0, st, p);
+  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((sattn_mfma<D, 2>), grid, dim3(kSaWaves * 64), 0, st, p);
   return hipGetLastError();
 }
 
@@ -497,16 +804,23 @@ hipError_t launch_score(const ScoreParams& p, hipStream_t st) {
     else
       e = (p.D == 128) ? launch_sattn_valu<float, 128>(p, st) : launch_sattn_valu<float, 64>(p, st);
     if (e != hipSuccess) return e;
-    const long long n = (long long)p.B * p.Nv;
-    hipLaunchKernelGGL(sattn_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (accumulate_only) {   // otherwise the fusion kernel finishes the attention mass itself
+      const long long n = (long long)p.B * p.Nv;
+      hipLaunchKernelGGL(sattn_finalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+      return hipGetLastError();
+    }
   }
-  if (accumulate_only) return hipSuccess;
   if (p.flags & (HIPPO_SCORE_TEMP | HIPPO_SCORE_SPA)) {
     const int ncy = (p.gh + p.ch - 1) / p.ch, ncx = (p.gw + p.cw - 1) / p.cw;
     dim3 grid(ncy * ncx, p.F, p.B);
-    if (p.dtype == HIPPO_DTYPE_BF16) hipLaunchKernelGGL(emb_scores<uint16_t>, grid, dim3(256), 0, st, p);
-    else hipLaunchKernelGGL(emb_scores<float>, grid, dim3(256), 0, st, p);
+    if (p.dtype == HIPPO_DTYPE_BF16) {
+      const int crop = p.ch * p.cw;
+      if (crop <= 32) hipLaunchKernelGGL(emb_scores_mfma32, grid, dim3(256), 0, st, p);
+      else if (crop <= 48) hipLaunchKernelGGL(emb_scores_mfma<3>, grid, dim3(256), 0, st, p);
+      else hipLaunchKernelGGL(emb_scores_mfma<4>, grid, dim3(256), 0, st, p);
+    } else {
+      hipLaunchKernelGGL(emb_scores<float>, grid, dim3(256), 0, st, p);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   hipLaunchKernelGGL(fuse_scores, dim3(p.F, p.B), dim3(256), 0, st, p);

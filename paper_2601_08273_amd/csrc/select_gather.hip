@@ -2,7 +2,7 @@
 // keep the top-k visual tokens; App. "Details of Experimental Setups": pruned video features are
 // removed from the draft model's input, everything else is kept).
 //
-// Selection is exact and deterministic: scores map to order-preserving 32-bit keys, a 4 x 8-bit
+// Selection is exact and deterministic: scores map to order-preserving 32-bit keys, a 12/12/8-bit
 // radix select finds the k-th largest key, and an index-ordered compaction emits every key above
 // it plus the first (lowest-index) ties.  All counting is integer, so there is no run-to-run
 // variation.
@@ -11,6 +11,9 @@
 namespace hippo {
 
 constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kKeysPerThread = 40;       // keys held in registers: sequences up to 40960 tokens
+constexpr int kBins = 4096;              // 12-bit digits (the last pass uses 256 of them)
 
 // larger score -> larger key; -0 == +0; NaN -> 0, below every number (-inf maps to 0x007fffff)
 __device__ __forceinline__ uint32_t score_key(float x) {
@@ -20,74 +23,163 @@ __device__ __forceinline__ uint32_t score_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// inclusive scan over the 1024 threads of the block (wave scan, then the 16 wave totals)
+__device__ __forceinline__ unsigned block_incl_scan(unsigned v, unsigned* wave_tot) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned n = __shfl_up(v, o, 64);
+    if (lane >= o) v += n;
+  }
+  __syncthreads();
+  if (lane == 63) wave_tot[wave] = v;
+  __syncthreads();
+  unsigned off = 0;
+  for (int w = 0; w < wave; ++w) off += wave_tot[w];
+  return v + off;
+}
+
+// One block per sequence.  CACHED: every thread keeps its keys (index c*1024 + tid) in registers,
+// so the scores are read from memory once; otherwise each pass re-reads them.
+// Radix select with digits of 12, 12 and 8 bits: the wide first digit (sign, exponent, 3 mantissa
+// bits) spreads scores of similar magnitude over many LDS bins, which keeps same-address atomic
+// traffic low.  The compaction is index-ordered: per-(chunk, wave) counts, one scan, then each key
+// computes its slot from the scan and its rank inside the wave.
+template <bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
-  __shared__ unsigned hist[256];
+  __shared__ unsigned hist[kBins];
+  __shared__ unsigned wave_tot[kSelWaves];
   __shared__ unsigned sh_prefix, sh_need;
-  __shared__ unsigned wave_gt[kSelThreads / 64], wave_eq[kSelThreads / 64];
-  __shared__ unsigned run_gt, run_eq;
 
   const int b = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const float* sc = p.scores + (long long)b * p.Nv;
   int32_t* out = p.idx_out + (long long)b * p.k;
+  const int n_chunks = (p.Nv + kSelThreads - 1) / kSelThreads;
+
+  unsigned keys[CACHED ? kKeysPerThread : 1];
+  if (CACHED) {
+#pragma unroll
+    for (int c = 0; c < kKeysPerThread; ++c) {
+      const int i = c * kSelThreads + tid;
+      keys[c] = (c < n_chunks && i < p.Nv) ? score_key(sc[i]) : 0u;
+    }
+  }
+  auto key_at = [&](int c) -> unsigned {     // key of chunk c for this thread (index must be < Nv)
+    return CACHED ? keys[c] : score_key(sc[c * kSelThreads + tid]);
+  };
 
   // ---- radix select of the k-th largest key ----
   unsigned prefix = 0, need = (unsigned)p.k;   // `need` keys still wanted among those matching prefix
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    if (tid < 256) hist[tid] = 0;
+  const int shifts[3] = {20, 8, 0};
+  const unsigned masks[3] = {0u, 0xfff00000u, 0xffffff00u};   // bits already decided
+  const unsigned dmask[3] = {0xfffu, 0xfffu, 0xffu};
+#pragma unroll
+  for (int pass = 0; pass < 3; ++pass) {
+    for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
     __syncthreads();
-    const unsigned hi_mask = (shift == 24) ? 0u : (0xffffffffu << (shift + 8));
-    for (int i = tid; i < p.Nv; i += kSelThreads) {
-      const unsigned key = score_key(sc[i]);
-      if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    if (CACHED) {
+#pragma unroll
+      for (int c = 0; c < kKeysPerThread; ++c)
+        if (c < n_chunks && c * kSelThreads + tid < p.Nv && (keys[c] & masks[pass]) == prefix)
+          atomicAdd(&hist[(keys[c] >> shifts[pass]) & dmask[pass]], 1u);
+    } else {
+      for (int c = 0; c < n_chunks; ++c)
+        if (c * kSelThreads + tid < p.Nv) {
+          const unsigned key = key_at(c);
+          if ((key & masks[pass]) == prefix) atomicAdd(&hist[(key >> shifts[pass]) & dmask[pass]], 1u);
+        }
     }
     __syncthreads();
-    if (tid == 0) {
-      unsigned above = 0;
-      int d = 255;
-      for (; d > 0; --d) {
-        if (above + hist[d] >= need) break;
-        above += hist[d];
-      }
-      sh_prefix = prefix | ((unsigned)d << shift);
+    // thread t looks at bins 4*(1023-t) .. +3 in descending order: an inclusive scan over t then
+    // counts the keys in all higher bins
+    const int top = kBins - 1 - 4 * tid;
+    const unsigned h0 = hist[top], h1 = hist[top - 1], h2 = hist[top - 2], h3 = hist[top - 3];
+    const unsigned incl = block_incl_scan(h0 + h1 + h2 + h3, wave_tot);
+    unsigned above = incl - (h0 + h1 + h2 + h3);          // keys in bins above this thread's four
+    if (above < need && incl >= need) {                   // exactly one thread
+      unsigned d = top, hh = h0;
+      if (above + hh < need) { above += hh; d = top - 1; hh = h1; }
+      if (above + hh < need) { above += hh; d = top - 2; hh = h2; }
+      if (above + hh < need) { above += hh; d = top - 3; }
+      sh_prefix = prefix | (d << shifts[pass]);
       sh_need = need - above;
     }
     __syncthreads();
     prefix = sh_prefix;
     need = sh_need;
-    __syncthreads();
   }
   const unsigned thr = prefix;      // the k-th largest key
   const unsigned need_eq = need;    // how many keys equal to it are kept (lowest indices first)
 
   // ---- compaction in index order ----
-  if (tid == 0) { run_gt = 0; run_eq = 0; }
+  // counts per (chunk, wave) in chunk-major order reuse the histogram storage: [2][n_chunks*16]
+  unsigned* cnt_gt = hist;
+  unsigned* cnt_eq = hist + kKeysPerThread * kSelWaves;
   __syncthreads();
-  const int lane = tid & 63, wave = tid >> 6;
-  for (int base = 0; base < p.Nv; base += kSelThreads) {
-    const int i = base + tid;
-    unsigned key = 0;
-    bool gt = false, eq = false;
-    if (i < p.Nv) {
-      key = score_key(sc[i]);
+  auto flags = [&](int c, bool& gt, bool& eq) {
+    gt = eq = false;
+    if (c * kSelThreads + tid < p.Nv) {
+      const unsigned key = key_at(c);
       gt = key > thr;
       eq = key == thr;
     }
-    const unsigned long long bg = __ballot(gt), be = __ballot(eq);
-    const unsigned long long below = (1ull << lane) - 1ull;
-    const unsigned my_gt = __popcll(bg & below), my_eq = __popcll(be & below);
-    if (lane == 0) { wave_gt[wave] = __popcll(bg); wave_eq[wave] = __popcll(be); }
-    __syncthreads();
-    unsigned off_gt = run_gt, off_eq = run_eq;
-    for (int w = 0; w < wave; ++w) { off_gt += wave_gt[w]; off_eq += wave_eq[w]; }
-    const unsigned gt_before = off_gt + my_gt, eq_before = off_eq + my_eq;
-    if (gt || (eq && eq_before < need_eq))
-      out[gt_before + min(eq_before, need_eq)] = i;
-    __syncthreads();
-    if (tid == kSelThreads - 1) {
-      run_gt = off_gt + my_gt + (gt ? 1u : 0u);
-      run_eq = off_eq + my_eq + (eq ? 1u : 0u);
+  };
+  if (CACHED) {
+#pragma unroll
+    for (int c = 0; c < kKeysPerThread; ++c) {
+      if (c < n_chunks) {
+        bool gt, eq;
+        flags(c, gt, eq);
+        const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+        if (lane == 0) { cnt_gt[c * kSelWaves + wave] = __popcll(bg); cnt_eq[c * kSelWaves + wave] = __popcll(be); }
+      }
     }
     __syncthreads();
+    // exclusive scan of both count arrays (at most 640 entries each): one entry per thread
+    const int n_ent = n_chunks * kSelWaves;
+    const unsigned vg = tid < n_ent ? cnt_gt[tid] : 0u, ve = tid < n_ent ? cnt_eq[tid] : 0u;
+    const unsigned ig = block_incl_scan(vg, wave_tot);
+    const unsigned ie = block_incl_scan(ve, wave_tot);
+    __syncthreads();
+    if (tid < n_ent) { cnt_gt[tid] = ig - vg; cnt_eq[tid] = ie - ve; }
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int c = 0; c < kKeysPerThread; ++c) {
+      if (c < n_chunks) {
+        bool gt, eq;
+        flags(c, gt, eq);
+        const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+        const unsigned gt_before = cnt_gt[c * kSelWaves + wave] + __popcll(bg & below);
+        const unsigned eq_before = cnt_eq[c * kSelWaves + wave] + __popcll(be & below);
+        if (gt || (eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = c * kSelThreads + tid;
+      }
+    }
+  } else {
+    // long sequences: chunk by chunk with running totals
+    __shared__ unsigned run_gt, run_eq, wg[kSelWaves], we[kSelWaves];
+    if (tid == 0) { run_gt = 0; run_eq = 0; }
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int c = 0; c < n_chunks; ++c) {
+      bool gt, eq;
+      flags(c, gt, eq);
+      const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+      const unsigned my_gt = __popcll(bg & below), my_eq = __popcll(be & below);
+      if (lane == 0) { wg[wave] = __popcll(bg); we[wave] = __popcll(be); }
+      __syncthreads();
+      unsigned off_gt = run_gt, off_eq = run_eq;
+      for (int w = 0; w < wave; ++w) { off_gt += wg[w]; off_eq += we[w]; }
+      const unsigned gt_before = off_gt + my_gt, eq_before = off_eq + my_eq;
+      if (gt || (eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = c * kSelThreads + tid;
+      __syncthreads();
+      if (tid == kSelThreads - 1) {
+        run_gt = off_gt + my_gt + (gt ? 1u : 0u);
+        run_eq = off_eq + my_eq + (eq ? 1u : 0u);
+      }
+      __syncthreads();
+    }
   }
 }
 
@@ -117,7 +209,8 @@ __global__ __launch_bounds__(256) void gather_kv(SelectParams p) {
 }
 
 hipError_t launch_select_gather(const SelectParams& p, hipStream_t st) {
-  hipLaunchKernelGGL(topk_select, dim3(p.B), dim3(kSelThreads), 0, st, p);
+  if (p.Nv <= kKeysPerThread * kSelThreads) hipLaunchKernelGGL(topk_select<true>, dim3(p.B), dim3(kSelThreads), 0, st, p);
+  else hipLaunchKernelGGL(topk_select<false>, dim3(p.B), dim3(kSelThreads), 0, st, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.k_dst == nullptr) return e;
   const long long total = (long long)p.B * p.Hkv * p.dst_len * (p.D * p.elem_bytes / 16);

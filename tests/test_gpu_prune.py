@@ -107,12 +107,14 @@ def select_case(hippo, scores: np.ndarray, k: int):
 
 
 @pytest.mark.parametrize("n,k", [(1, 1), (63, 7), (64, 64), (1025, 100), (4096, 410), (16384, 1639),
-                                 (36864, 3687), (36864, 36863), (5000, 1)])
+                                 (36864, 3687), (36864, 36863), (5000, 1), (40960, 4096), (40961, 7),
+                                 (70001, 7001)])
 def test_topk_bit_exact(hippo, n, k):
     select_case(hippo, si.random_scores(2, n, n + k), k)
 
 
-@pytest.mark.parametrize("n,k,distinct", [(1000, 100, 3), (4096, 2048, 2), (777, 776, 1), (20000, 5000, 17)])
+@pytest.mark.parametrize("n,k,distinct", [(1000, 100, 3), (4096, 2048, 2), (777, 776, 1), (20000, 5000, 17),
+                                          (50000, 20000, 5)])
 def test_topk_with_many_ties(hippo, n, k, distinct):
     select_case(hippo, si.random_scores(3, n, n, n_distinct=distinct), k)
 
