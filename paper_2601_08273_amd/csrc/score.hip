@@ -580,20 +580,24 @@ __global__ __launch_bounds__(256) void emb_scores_mfma(ScoreParams p) {
 
 // =================================================================================================
 // s_temp and s_spa on MFMA, crops of at most 32 tokens (the paper's 5 x 5): channel-split variant.
-// Same products as emb_scores_mfma, but here the 4 waves split the CHANNELS (wave w takes channel
-// steps w, w+4, ...), so every operand is fetched from memory exactly once per block; the waves'
-// partial 16x16 blocks are summed through LDS.
+// Same products as emb_scores_mfma, but here the waves split the CHANNELS in two halves and the
+// neighbour frames between them (waves 0,1: Gram and previous frame; waves 2,3: next frame), so an
+// operand is fetched at most twice per block; the two channel halves are summed through LDS.
 // =================================================================================================
 __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
   constexpr int MP = 32;
-  constexpr int NBLK = 11;   // Gram (0,0) (0,1) (1,1); then for prev and next: dot rb0, dot rb1, norm rb0, norm rb1
-  __shared__ f32x4 red[4][NBLK][64];
+  // blocks: Gram (0,0) (0,1) (1,1); then for prev and for next: dot rb0, dot rb1, norm rb0, norm rb1
+  constexpr int NBLK = 11;
+  __shared__ f32x4 red[2][NBLK][64];                // partial blocks of the two channel halves
   __shared__ float G[MP][MP + 1];
   __shared__ float tdot[4][MP];
+  __shared__ float inv_norm[MP];
   __shared__ int tok_s[MP];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cg = wave & 1;                          // channel half: channel steps cg, cg+2, ...
+  const int ig = wave >> 1;                         // 0: Gram + previous frame, 1: next frame
   const int j = lane & 15, g = lane >> 4;
   const int ncx = (p.gw + p.cw - 1) / p.cw;
   const int cy = blockIdx.x / ncx, cx = blockIdx.x % ncx;
@@ -611,7 +615,7 @@ __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
   __syncthreads();
 
   // frames without a neighbour re-read the frame itself (finite data, result unused)
-  const int dprev = has_prev ? -1 : 0, dnext = has_next ? 1 : 0;
+  const int dnb = ig == 0 ? (has_prev ? -1 : 0) : (has_next ? 1 : 0);
   auto operand = [&](int df, int rbk, int ks) -> bf16x8 {
     const int c = ks * 32 + g * 8;
     if (ks >= n_ks || c >= de) return (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
@@ -627,39 +631,43 @@ __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
     return *(const bf16x8*)src;
   };
 
-  f32x4 acc[NBLK];
+  f32x4 acc[7];   // ig 0: Gram x3, dot x2, norm x2;  ig 1: (unused x3), dot x2, norm x2
 #pragma unroll
-  for (int i = 0; i < NBLK; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  for (int ks0 = wave; ks0 < n_ks; ks0 += 16) {       // 4 channel steps of this wave per round
-    bf16x8 cur[4][2], prv[4][2], nxt[4][2];
+  for (int i = 0; i < 7; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int ks0 = cg; ks0 < n_ks; ks0 += 8) {        // 4 channel steps of this wave per round
+    bf16x8 cur[4][2], nb[4][2];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int rbk = 0; rbk < 2; ++rbk) {
-        cur[u][rbk] = operand(0, rbk, ks0 + 4 * u);
-        prv[u][rbk] = operand(dprev, rbk, ks0 + 4 * u);
-        nxt[u][rbk] = operand(dnext, rbk, ks0 + 4 * u);
+        cur[u][rbk] = operand(0, rbk, ks0 + 2 * u);
+        nb[u][rbk] = operand(dnb, rbk, ks0 + 2 * u);
       }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][0], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][1], acc[1], 0, 0, 0);
-      acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][1], cur[u][1], acc[2], 0, 0, 0);
+      if (ig == 0) {
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][0], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][1], acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][1], cur[u][1], acc[2], 0, 0, 0);
+      }
 #pragma unroll
       for (int rbk = 0; rbk < 2; ++rbk) {
-        acc[3 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][rbk], prv[u][rbk], acc[3 + rbk], 0, 0, 0);
-        acc[5 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(prv[u][rbk], prv[u][rbk], acc[5 + rbk], 0, 0, 0);
-        acc[7 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][rbk], nxt[u][rbk], acc[7 + rbk], 0, 0, 0);
-        acc[9 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(nxt[u][rbk], nxt[u][rbk], acc[9 + rbk], 0, 0, 0);
+        acc[3 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][rbk], nb[u][rbk], acc[3 + rbk], 0, 0, 0);
+        acc[5 + rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(nb[u][rbk], nb[u][rbk], acc[5 + rbk], 0, 0, 0);
       }
     }
   }
+  if (ig == 0) {
 #pragma unroll
-  for (int i = 0; i < NBLK; ++i) red[wave][i][lane] = acc[i];
+    for (int i = 0; i < 7; ++i) red[cg][i][lane] = acc[i];
+  } else {
+#pragma unroll
+    for (int i = 3; i < 7; ++i) red[cg][4 + i][lane] = acc[i];
+  }
   __syncthreads();
-  // sum the 4 waves; thread (blk = tid/64 + 4x, lane) finishes block blk
+  // sum the two channel halves; wave w finishes blocks w, w+4, ...
   for (int blk = wave; blk < NBLK; blk += 4) {
-    const f32x4 v = red[0][blk][lane] + red[1][blk][lane] + red[2][blk][lane] + red[3][blk][lane];
+    const f32x4 v = red[0][blk][lane] + red[1][blk][lane];
     // D[i][j']: this lane holds column j' = j, rows i = 4g..4g+3
     if (blk < 3) {
       const int ra = blk == 2 ? 1 : 0, rbk = blk == 0 ? 0 : 1;
@@ -674,20 +682,18 @@ __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
     }
   }
   __syncthreads();
+  if (tid < MP) inv_norm[tid] = G[tid][tid] > 0.f ? 1.f / sqrtf(G[tid][tid]) : 0.f;   // 0: zero-norm row
+  __syncthreads();
 
   if (tid < M) {
     const int a = tid;
-    const float na = G[a][a];
+    const float ia = inv_norm[a];
     float mu = 0.f;
-    for (int c2 = 0; c2 < M; ++c2) {
-      const float nb = G[c2][c2];
-      mu += (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
-    }
+    for (int c2 = 0; c2 < M; ++c2) mu += G[a][c2] * ia * inv_norm[c2];
     mu /= (float)M;
     float var = 0.f;
     for (int c2 = 0; c2 < M; ++c2) {
-      const float nb = G[c2][c2];
-      const float cs = (na > 0.f && nb > 0.f) ? G[a][c2] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      const float cs = G[a][c2] * ia * inv_norm[c2];
       var = fmaf(cs - mu, cs - mu, var);
     }
     const long long o = (long long)b * p.Nv + tok_s[a];
@@ -695,13 +701,13 @@ __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
     float sum = 0.f;
     int cnt = 0;
     if (has_prev) {
-      const float nb = tdot[1][a];
-      sum += (na > 0.f && nb > 0.f) ? tdot[0][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      const float nb2 = tdot[1][a];
+      sum += (nb2 > 0.f) ? tdot[0][a] * ia / sqrtf(nb2) : 0.f;
       ++cnt;
     }
     if (has_next) {
-      const float nb = tdot[3][a];
-      sum += (na > 0.f && nb > 0.f) ? tdot[2][a] / (sqrtf(na) * sqrtf(nb)) : 0.f;
+      const float nb2 = tdot[3][a];
+      sum += (nb2 > 0.f) ? tdot[2][a] * ia / sqrtf(nb2) : 0.f;
       ++cnt;
     }
     p.s_temp[o] = 1.f - (cnt ? sum / (float)cnt : 0.f);

@@ -14,6 +14,7 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kKeysPerThread = 40;       // keys held in registers: sequences up to 40960 tokens
 constexpr int kBins = 4096;              // 12-bit digits (the last pass uses 256 of them)
+constexpr int kBinsPerThread = kBins / kSelThreads;
 
 // larger score -> larger key; -0 == +0; NaN -> 0, below every number (-inf maps to 0x007fffff)
 __device__ __forceinline__ uint32_t score_key(float x) {
@@ -39,14 +40,16 @@ __device__ __forceinline__ unsigned block_incl_scan(unsigned v, unsigned* wave_t
   return v + off;
 }
 
-// One block per sequence.  CACHED: every thread keeps its keys (index c*1024 + tid) in registers,
-// so the scores are read from memory once; otherwise each pass re-reads them.
+// One block per sequence.  NC > 0: every thread keeps its keys (index c*1024 + tid, c < NC) in
+// registers, so the scores are read from memory once and every loop over them is unrolled to the
+// sequence's size class; NC = 0: any length, each pass re-reads the scores.
 // Radix select with digits of 12, 12 and 8 bits: the wide first digit (sign, exponent, 3 mantissa
 // bits) spreads scores of similar magnitude over many LDS bins, which keeps same-address atomic
 // traffic low.  The compaction is index-ordered: per-(chunk, wave) counts, one scan, then each key
 // computes its slot from the scan and its rank inside the wave.
-template <bool CACHED>
+template <int NC>
 __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
+  constexpr bool CACHED = NC > 0;
   __shared__ unsigned hist[kBins];
   __shared__ unsigned wave_tot[kSelWaves];
   __shared__ unsigned sh_prefix, sh_need;
@@ -57,10 +60,10 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   int32_t* out = p.idx_out + (long long)b * p.k;
   const int n_chunks = (p.Nv + kSelThreads - 1) / kSelThreads;
 
-  unsigned keys[CACHED ? kKeysPerThread : 1];
+  unsigned keys[CACHED ? NC : 1];
   if (CACHED) {
 #pragma unroll
-    for (int c = 0; c < kKeysPerThread; ++c) {
+    for (int c = 0; c < NC; ++c) {
       const int i = c * kSelThreads + tid;
       keys[c] = (c < n_chunks && i < p.Nv) ? score_key(sc[i]) : 0u;
     }
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     __syncthreads();
     if (CACHED) {
 #pragma unroll
-      for (int c = 0; c < kKeysPerThread; ++c)
+      for (int c = 0; c < NC; ++c)
         if (c < n_chunks && c * kSelThreads + tid < p.Nv && (keys[c] & masks[pass]) == prefix)
           atomicAdd(&hist[(keys[c] >> shifts[pass]) & dmask[pass]], 1u);
     } else {
@@ -91,17 +94,21 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
         }
     }
     __syncthreads();
-    // thread t looks at bins 4*(1023-t) .. +3 in descending order: an inclusive scan over t then
-    // counts the keys in all higher bins
-    const int top = kBins - 1 - 4 * tid;
-    const unsigned h0 = hist[top], h1 = hist[top - 1], h2 = hist[top - 2], h3 = hist[top - 3];
-    const unsigned incl = block_incl_scan(h0 + h1 + h2 + h3, wave_tot);
-    unsigned above = incl - (h0 + h1 + h2 + h3);          // keys in bins above this thread's four
+    // thread t looks at its kBinsPerThread bins from the top down, thread 0 holding the highest:
+    // an inclusive scan over t then counts the keys in all higher bins
+    const int top = kBins - 1 - kBinsPerThread * tid;
+    unsigned hsum = 0;
+#pragma unroll
+    for (int q = 0; q < kBinsPerThread; ++q) hsum += hist[top - q];
+    const unsigned incl = block_incl_scan(hsum, wave_tot);
+    unsigned above = incl - hsum;                         // keys in bins above this thread's
     if (above < need && incl >= need) {                   // exactly one thread
-      unsigned d = top, hh = h0;
-      if (above + hh < need) { above += hh; d = top - 1; hh = h1; }
-      if (above + hh < need) { above += hh; d = top - 2; hh = h2; }
-      if (above + hh < need) { above += hh; d = top - 3; }
+      unsigned d = top;
+#pragma unroll
+      for (int q = 0; q < kBinsPerThread - 1; ++q) {
+        const unsigned hh = hist[top - q];
+        if (d == (unsigned)(top - q) && above + hh < need) { above += hh; d = top - q - 1; }
+      }
       sh_prefix = prefix | (d << shifts[pass]);
       sh_need = need - above;
     }
@@ -127,7 +134,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   };
   if (CACHED) {
 #pragma unroll
-    for (int c = 0; c < kKeysPerThread; ++c) {
+    for (int c = 0; c < NC; ++c) {
       if (c < n_chunks) {
         bool gt, eq;
         flags(c, gt, eq);
@@ -136,17 +143,26 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
       }
     }
     __syncthreads();
-    // exclusive scan of both count arrays (at most 640 entries each): one entry per thread
+    // exclusive scan of both count arrays in (chunk, wave) order; n_chunks * waves <= 640 entries,
+    // handled kSelThreads at a time with a running carry
     const int n_ent = n_chunks * kSelWaves;
-    const unsigned vg = tid < n_ent ? cnt_gt[tid] : 0u, ve = tid < n_ent ? cnt_eq[tid] : 0u;
-    const unsigned ig = block_incl_scan(vg, wave_tot);
-    const unsigned ie = block_incl_scan(ve, wave_tot);
-    __syncthreads();
-    if (tid < n_ent) { cnt_gt[tid] = ig - vg; cnt_eq[tid] = ie - ve; }
-    __syncthreads();
+    unsigned carry_g = 0, carry_e = 0;
+    for (int e0 = 0; e0 < n_ent; e0 += kSelThreads) {
+      const int e = e0 + tid;
+      const unsigned vg = e < n_ent ? cnt_gt[e] : 0u, ve = e < n_ent ? cnt_eq[e] : 0u;
+      const unsigned ig = block_incl_scan(vg, wave_tot);
+      const unsigned ie = block_incl_scan(ve, wave_tot);
+      __syncthreads();
+      if (e < n_ent) { cnt_gt[e] = carry_g + ig - vg; cnt_eq[e] = carry_e + ie - ve; }
+      if (tid == kSelThreads - 1) { sh_prefix = ig; sh_need = ie; }
+      __syncthreads();
+      carry_g += sh_prefix;
+      carry_e += sh_need;
+      __syncthreads();
+    }
     const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int c = 0; c < kKeysPerThread; ++c) {
+    for (int c = 0; c < NC; ++c) {
       if (c < n_chunks) {
         bool gt, eq;
         flags(c, gt, eq);
@@ -209,8 +225,17 @@ __global__ __launch_bounds__(256) void gather_kv(SelectParams p) {
 }
 
 hipError_t launch_select_gather(const SelectParams& p, hipStream_t st) {
-  if (p.Nv <= kKeysPerThread * kSelThreads) hipLaunchKernelGGL(topk_select<true>, dim3(p.B), dim3(kSelThreads), 0, st, p);
-  else hipLaunchKernelGGL(topk_select<false>, dim3(p.B), dim3(kSelThreads), 0, st, p);
+  const int n_chunks = (p.Nv + kSelThreads - 1) / kSelThreads;
+#define HIPPO_TOPK(NC_) hipLaunchKernelGGL(topk_select<NC_>, dim3(p.B), dim3(kSelThreads), 0, st, p)
+  if (n_chunks <= 2) HIPPO_TOPK(2);
+  else if (n_chunks <= 4) HIPPO_TOPK(4);
+  else if (n_chunks <= 8) HIPPO_TOPK(8);
+  else if (n_chunks <= 16) HIPPO_TOPK(16);
+  else if (n_chunks <= 24) HIPPO_TOPK(24);
+  else if (n_chunks <= 32) HIPPO_TOPK(32);
+  else if (n_chunks <= kKeysPerThread) HIPPO_TOPK(kKeysPerThread);
+  else HIPPO_TOPK(0);
+#undef HIPPO_TOPK
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.k_dst == nullptr) return e;
   const long long total = (long long)p.B * p.Hkv * p.dst_len * (p.D * p.elem_bytes / 16);
