@@ -50,6 +50,8 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -208,6 +210,13 @@ def main():
     t_draft_alone = alone(run_draft) / L
     t_score_alone = alone(run_score)
     t_prune_alone = alone(run_prune)
+
+    if args.pmc_calibration:       # a plain copy of known size: reads 256 MiB, writes 256 MiB
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     traffic = None    # HBM bytes per verify call from a counter run, if one has been summarised
     tf = os.path.join(ROOT, "profiles", "verify_attention_%s_hbm_traffic.txt" % args.workload)
