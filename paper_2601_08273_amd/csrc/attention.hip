@@ -261,7 +261,8 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   constexpr int RPS = 256 / ROWB;
   constexpr int NQ = RB * 16 / RPI;                    // transfers for the query block
   constexpr int XFERS = TG * 2 * NLD;                  // transfers per super-tile
-  constexpr int ISSUERS = WAVES < 8 ? (XFERS < WAVES ? XFERS : WAVES) : (XFERS < 8 ? XFERS : 8);
+  constexpr int ISS0 = WAVES >= 8 ? 8 : (WAVES >= 4 ? 4 : (WAVES >= 2 ? 2 : 1));   // power of two <= WAVES
+  constexpr int ISSUERS = XFERS < ISS0 ? XFERS : ISS0;
   constexpr int PER = XFERS / ISSUERS;                 // transfers per issuing wave per super-tile
   static_assert(XFERS % ISSUERS == 0 && PER * (NST - 1) <= 63, "transfer split");
   static_assert(DB % TG == 0, "head-dim blocks must split over the token groups");
@@ -593,13 +594,24 @@ static hipError_t launch_grid(const AttnParams& p, hipStream_t st) {
 }
 
 // Short slices (a block owns only a handful of tiles, as at 16K context on 256 compute units) use
-// 16-token tiles and a three-stage ring: the first data then arrives early enough for the math to
-// overlap the rest of the stream.  Long slices use 32-token tiles, which halve the barrier count.
+// 16-token tiles and a deeper ring; long slices use 32-token tiles, which halve the barrier count.
 template <int D, int RB>
 static hipError_t launch_grid_rb(const AttnParams& p, hipStream_t st) {
   const int tiles32_per_block = ((p.n_total + 31) / 32) / (p.S > 0 ? p.S : 1);
   const bool small_tiles = p.variant == 1 || (p.variant != 2 && tiles32_per_block < 24);
-  return small_tiles ? launch_grid<D, RB, 4, 16, 3>(p, st) : launch_grid<D, RB, 4, 32, 2>(p, st);
+#ifdef HIPPO_TUNE
+  if (p.variant == 10) return launch_grid<D, RB, 2, 16, 3>(p, st);
+  if (p.variant == 11) return launch_grid<D, RB, 4, 16, 3>(p, st);
+  if (p.variant == 12) return launch_grid<D, RB, 4, 16, 4>(p, st);
+  if (p.variant == 13) return launch_grid<D, RB, 2, 32, 2>(p, st);
+  if (p.variant == 14) return launch_grid<D, RB, 2, 32, 3>(p, st);
+  if (p.variant == 15) return launch_grid<D, RB, 4, 16, 2>(p, st);
+#endif
+  if (!small_tiles) return launch_grid<D, RB, 4, 32, 2>(p, st);
+  // measured at the 16K configuration: with 3-4 row blocks, two token groups and a four-stage ring
+  // (the whole slice in flight at once) beat four groups by ~8 %; the block merge moves half the data
+  if (RB >= 3) return launch_grid<D, RB, 2, 16, 4>(p, st);
+  return launch_grid<D, RB, 4, 16, 3>(p, st);
 }
 
 template <int D>
