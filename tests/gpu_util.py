@@ -3,10 +3,11 @@
 Tolerances (stated by the benchmark definition, with the reading used for values that cross zero):
   fp32 : |x - ref| <= 1e-5 * max(|ref|, rms(ref))
   bf16 : |x - ref| <= 2e-2 + 2e-2 * |ref|
-and, because attention outputs on these inputs are far smaller than 2e-2, a second, tighter bound
-derived from the kernel's arithmetic (P rounded to bf16 before the PV product: relative 2^-9 per
-term; output rounded to bf16: relative 2^-9; everything else fp32):
-  bf16 : |x - ref| <= 1e-2 * max(|ref|, rms(ref))
+and, because attention outputs on these inputs are far smaller than 2e-2, a second bound without
+the absolute term, derived from the kernel's arithmetic (P rounded to bf16 before the PV product:
+relative 2^-9 per term, so up to 2^-9 * sum_n p_n |v_n|, which under cancellation is a few times
+2^-9 |out|; output rounded to bf16: relative 2^-9; everything else fp32):
+  bf16 : |x - ref| <= 2e-2 * max(|ref|, rms(ref))
 """
 import numpy as np
 import torch
@@ -42,7 +43,7 @@ def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = ""):
     if dtype == "fp32":
         bad = err > 1e-5 * floor
     else:
-        bad = (err > 2e-2 + 2e-2 * np.abs(ref)) | (err > 1e-2 * floor)
+        bad = (err > 2e-2 + 2e-2 * np.abs(ref)) | (err > 2e-2 * floor)
     if bad.any():
         i = np.unravel_index(np.argmax(err / np.maximum(floor, 1e-300)), err.shape)
         raise AssertionError("%s: %d of %d outside tolerance; worst at %s got %.9g ref %.9g (rms %.3g)"
