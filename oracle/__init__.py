@@ -46,6 +46,7 @@ _SIGS = {
     "hippo_oracle_topk": [_VP, _I, _I, _I, _VP],
     "hippo_oracle_gather": [_VP, _I, _I, _I, _I, _I, _I, _VP, _I, _VP],
     "hippo_oracle_attention": [_VP, _I, _I, _I, _I, _I, _VP, _VP, _I64, _I64, _I, _D, _VP, _VP],
+    "hippo_oracle_spec_verify": [_VP, _VP, _VP, _VP, _VP, _I, _I, _I, _D, _VP, _VP, _VP],
 }
 
 
@@ -182,3 +183,30 @@ def attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, ctx_len: 
                                 C.c_int64(Hkv * N * d), C.c_int64(N * d), ctx_len,
                                 C.c_double(scale), _p(out), _p(lse))
     return out, lse
+
+
+def spec_verify(p_logits: np.ndarray, q_logits: Optional[np.ndarray], tokens: np.ndarray,
+                u_accept: np.ndarray, u_sample: np.ndarray, temperature: float
+                ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Eq. 1 + resampling.  p_logits [B,gamma+1,V], q_logits [B,gamma,V] (None allowed when
+    temperature == 0), tokens [B,gamma] int32, u_accept [B,gamma], u_sample [B].
+    Returns (n_accept [B] int32, next_token [B] int32, alpha [B,gamma] float64)."""
+    p_logits = _f32(p_logits)
+    B, g1, V = p_logits.shape
+    gamma = g1 - 1
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32).reshape(B, gamma)
+    assert tokens.min(initial=0) >= 0 and tokens.max(initial=0) < V
+    if q_logits is not None:
+        q_logits = _f32(q_logits)
+        assert q_logits.shape == (B, gamma, V)
+    else:
+        assert temperature == 0
+    u_accept = _f32(u_accept).reshape(B, gamma)
+    u_sample = _f32(u_sample).reshape(B)
+    n_acc = np.zeros(B, dtype=np.int32)
+    nxt = np.full(B, -1, dtype=np.int32)
+    alpha = np.zeros((B, gamma), dtype=np.float64)
+    _L().hippo_oracle_spec_verify(_p(p_logits), None if q_logits is None else _p(q_logits), _p(tokens),
+                                  _p(u_accept), _p(u_sample), B, gamma, V, C.c_double(temperature),
+                                  _p(n_acc), _p(nxt), _p(alpha))
+    return n_acc, nxt, alpha

@@ -15,6 +15,9 @@
  *
  * Pins (tests/test_oracle_pins.py): closed forms and invariants of Eq. 2-7, brute-force top-k,
  * textbook softmax(QK^T)V through a library routine, truncation / gamma = 0 identities.
+ * Pins of the speculative-sampling verification, Eq. 1 (tests/test_oracle_sd_pins.py): the emitted
+ * token follows the target distribution for any draft distribution, acceptance rate
+ * sum min(p, q), a hand-worked example, inverse-CDF boundaries, greedy limit by brute force.
  * Agreement with the authors' own code is UNPINNED: the paper prints no code and no worked
  * numbers, so the readings listed next to each function are this build's.
  */
@@ -286,4 +289,96 @@ void hippo_oracle_attention(const float *q, int B, int q_len, int H, int Hkv, in
             }
             free(p);
         }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Eq. 1 and the resampling rule below it -- speculative-sampling verification of one chain of
+ * gamma draft tokens (Preliminaries, "Speculative Decoding").
+ *
+ *   p_i = softmax(p_logits[i] / T), i = 0..gamma   (target: row i is the distribution of the token
+ *                                                   that follows prefix + x_1..x_i)
+ *   q_i = softmax(q_logits[i] / T), i = 0..gamma-1 (draft: row i is what x_{i+1} was sampled from)
+ * Reading of the paper's indices (it numbers gamma+1 target rows 0..gamma but verifies x_i with
+ * "p_i", and conditions q_i on x_i itself): draft token number i (0-based) is verified by row i of
+ * both models, and the extra token after a full acceptance comes from the last target row,
+ * which is the one the paper names p_gamma.
+ *   alpha_i = 1 if p_i[x_i] >= q_i[x_i], else p_i[x_i] / q_i[x_i]               (Eq. 1)
+ *   token i is accepted iff u_accept[i] < alpha_i, u in [0, 1); verification stops at the first
+ *   rejection j, and the replacement is drawn from r = max(0, p_j - q_j) / sum(max(0, p_j - q_j));
+ *   with no rejection the extra token is drawn from p_gamma.
+ * Drawing from a distribution r with a uniform u: the first index t whose running sum
+ * r_0 + .. + r_t exceeds u * sum(r) (inverse CDF in index order); if rounding leaves none, the last
+ * index with r_t > 0.  If sum(max(0, p_j - q_j)) is 0 (p_j == q_j, reachable only through rounding)
+ * the replacement is drawn from p_j.
+ * T == 0 is greedy decoding, the T -> 0 limit: p_i is one-hot at the first maximum of
+ * p_logits[i], q_i is one-hot at x_i (a greedy draft emits its own argmax), and the same rules
+ * apply: alpha is 1 or 0 and the replacement / extra token is the target's argmax.
+ * alpha is reported for every position, also those after the first rejection.
+ */
+static void softmax_row(const float *logits, int V, double T, int onehot_at, double *out)
+{
+    if (T == 0.0) {
+        int a = onehot_at;
+        if (a < 0) {
+            a = 0;
+            for (int v = 1; v < V; ++v)
+                if ((double)logits[v] > (double)logits[a]) a = v;
+        }
+        for (int v = 0; v < V; ++v) out[v] = (v == a) ? 1.0 : 0.0;
+        return;
+    }
+    double m = -INFINITY, z = 0.0;
+    for (int v = 0; v < V; ++v)
+        if ((double)logits[v] / T > m) m = (double)logits[v] / T;
+    for (int v = 0; v < V; ++v) z += exp((double)logits[v] / T - m);
+    for (int v = 0; v < V; ++v) out[v] = exp((double)logits[v] / T - m) / z;
+}
+
+static int draw(const double *r, int V, double u)
+{
+    double total = 0.0, run = 0.0;
+    int last = -1;
+    for (int v = 0; v < V; ++v) total += r[v];
+    for (int v = 0; v < V; ++v) {
+        run += r[v];
+        if (r[v] > 0.0) last = v;
+        if (run > u * total) return v;
+    }
+    return last;
+}
+
+void hippo_oracle_spec_verify(const float *p_logits, const float *q_logits, const int32_t *tokens,
+                              const float *u_accept, const float *u_sample, int B, int gamma, int V,
+                              double T, int32_t *n_accept, int32_t *next_token, double *alpha)
+{
+#pragma omp parallel for schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        double *p = (double *)malloc(sizeof(double) * (size_t)V * 3);
+        double *q = p + V, *r = q + V;
+        int rejected = -1;
+        for (int i = 0; i < gamma; ++i) {
+            int x = tokens[(size_t)b * gamma + i];
+            softmax_row(p_logits + ((size_t)b * (gamma + 1) + i) * V, V, T, -1, p);
+            softmax_row(q_logits ? q_logits + ((size_t)b * gamma + i) * V : NULL, V, T, x, q);
+            double a = (p[x] >= q[x]) ? 1.0 : p[x] / q[x];
+            alpha[(size_t)b * gamma + i] = a;
+            if (rejected < 0 && !((double)u_accept[(size_t)b * gamma + i] < a)) {
+                rejected = i;
+                double total = 0.0;
+                for (int v = 0; v < V; ++v) {
+                    r[v] = p[v] - q[v] > 0.0 ? p[v] - q[v] : 0.0;
+                    total += r[v];
+                }
+                next_token[b] = draw(total > 0.0 ? r : p, V, (double)u_sample[b]);
+            }
+        }
+        if (rejected < 0) {
+            softmax_row(p_logits + ((size_t)b * (gamma + 1) + gamma) * V, V, T, -1, p);
+            next_token[b] = draw(p, V, (double)u_sample[b]);
+            n_accept[b] = gamma;
+        } else {
+            n_accept[b] = rejected;
+        }
+        free(p);
+    }
 }
