@@ -148,6 +148,31 @@ def main():
     def score_only():
         h.hippo_score_tokens(q_txt, kd[0][:, :, :n_ctx], vid, scores_out=scores, workspace=ws_score)
 
+    # speculative-sampling verification of the round's gamma draft tokens over LM-head-sized logits
+    # (outside the timed step: it widens the path beyond the attention calls the metric is quoted on)
+    V = si.LM_VOCAB
+    pl_h, ql_h, rng = si.make_logits(B, cfg.gamma, V, 0)
+    p_log, q_log = dev(pl_h, dt), dev(ql_h, dt)
+    sd_tok = torch.from_numpy(rng.integers(0, V, (B, cfg.gamma)).astype(np.int32)).cuda()
+    sd_ua = torch.from_numpy(rng.random((B, cfg.gamma), dtype=np.float32)).cuda()
+    sd_us = torch.from_numpy(rng.random(B, dtype=np.float32)).cuda()
+    sd_nacc = torch.empty(B, dtype=torch.int32, device="cuda")
+    sd_next = torch.empty(B, dtype=torch.int32, device="cuda")
+    ws_sd = torch.empty(h.load().hippo_spec_verify_workspace_bytes(B, cfg.gamma, V, h._dtype_code(p_log)),
+                        dtype=torch.uint8, device="cuda")
+
+    SD_REPS = 20        # calls per graph, so that the graph's own launch cost is amortised as for the layers
+
+    def spec_sampling():
+        for _ in range(SD_REPS):
+            h.hippo_spec_verify(p_log, q_log, sd_tok, sd_ua, sd_us, 1.0, n_accept_out=sd_nacc,
+                                next_token_out=sd_next, workspace=ws_sd)
+
+    def spec_greedy():
+        for _ in range(SD_REPS):
+            h.hippo_spec_verify(p_log, None, sd_tok, None, None, 0.0, n_accept_out=sd_nacc,
+                                next_token_out=sd_next, workspace=ws_sd)
+
     def capture(fn):
         fn()                                        # eager once (also sets kernel attributes)
         torch.cuda.synchronize()
@@ -163,6 +188,8 @@ def main():
     run_verify = capture(verify_all)
     run_draft = capture(draft_all)
     run_score = capture(score_only)
+    run_sd_sampling = capture(spec_sampling)
+    run_sd_greedy = capture(spec_greedy)
     torch.cuda.synchronize()
 
     def ev():
@@ -210,6 +237,8 @@ def main():
     t_draft_alone = alone(run_draft) / L
     t_score_alone = alone(run_score)
     t_prune_alone = alone(run_prune)
+    t_sd_sampling = alone(run_sd_sampling) / SD_REPS
+    t_sd_greedy = alone(run_sd_greedy) / SD_REPS
 
     if args.pmc_calibration:       # a plain copy of known size: reads 256 MiB, writes 256 MiB
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -251,7 +280,9 @@ def main():
                "alone:verify_per_layer": round(t_verify_alone * 1e6, 3),
                "alone:draft_per_layer": round(t_draft_alone * 1e6, 3),
                "alone:score_tokens": round(t_score_alone * 1e6, 2),
-               "alone:prune": round(t_prune_alone * 1e6, 2)},
+               "alone:prune": round(t_prune_alone * 1e6, 2),
+               "alone:spec_verify(sampling, V=%d)" % V: round(t_sd_sampling * 1e6, 2),
+               "alone:spec_verify(greedy, V=%d)" % V: round(t_sd_greedy * 1e6, 2)},
         "verify_alone_GBps": round(kv_bytes / t_verify_alone / 1e9, 1),
         "roofline": {"bound": "hbm", "achieved": round(verify_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(verify_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,

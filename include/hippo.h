@@ -178,6 +178,43 @@ int hippo_draft_attention(const void* q, int32_t q_len,
                           void* out, float* lse_out,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Speculative-sampling verification of one chain of gamma draft tokens per sequence
+ * (Preliminaries, "Speculative Decoding": Eq. 1, the resampling rule below it, and the extra token
+ * after a full acceptance; Method, "Adaptive Decoding Strategy Switching": conservative mode
+ * verifies x_1 alone, i.e. gamma = 1).
+ *   p_i = softmax(p_logits[b, i, :] / temperature), i = 0..gamma    target rows
+ *   q_i = softmax(q_logits[b, i, :] / temperature), i = 0..gamma-1  draft rows; draft token
+ *         x_i = draft_tokens[b, i] was sampled from q_i and is verified against p_i
+ *   alpha_i = 1 if p_i[x_i] >= q_i[x_i] else p_i[x_i] / q_i[x_i]                          (Eq. 1)
+ *   token i is accepted iff u_accept[b, i] < alpha_i; n_accept_out[b] = j = the first rejected
+ *   position (gamma if none).  next_token_out[b] is drawn with u_sample[b] from
+ *   max(0, p_j - q_j) / sum (from p_j if that sum is 0) after a rejection, from p_gamma otherwise:
+ *   the first word t whose running sum r_0 + .. + r_t exceeds u_sample * sum(r), in index order.
+ *   The caller emits x_0 .. x_{j-1} followed by next_token.
+ * temperature == 0 is greedy decoding (the paper's evaluation setting): p_i is one-hot at the first
+ *   maximum of its row, q_i one-hot at x_i, so alpha_i = [x_i == argmax p_i] and next_token is the
+ *   argmax of row j; q_logits, u_accept and u_sample are not read and may be NULL.
+ * alpha_out (optional) [B, gamma] fp32: alpha_i for every position, also after the first rejection.
+ * A draft token outside [0, vocab) is rejected (alpha 0).  Logits may be -inf (masked words) but
+ * not NaN or +inf, and every row needs a finite entry.  The uniforms are the caller's, in [0, 1).
+ *
+ * p_logits [B, gamma+1, p_stride_row], q_logits [B, gamma, q_stride_row], dtype F32 or BF16, row
+ * strides in elements, >= vocab and keeping rows 16-byte aligned; the first `vocab` entries of a
+ * row are read.  draft_tokens [B, gamma] int32, u_accept [B, gamma] fp32, u_sample [B] fp32,
+ * outputs int32 [B].  0 <= gamma <= 64 (gamma = 0 just draws from p_0), vocab <= 2^20.
+ * Sums are fp32; a word that the exact arithmetic would draw can be replaced by a neighbour in
+ * the running sum only when u_sample * sum lies within fp32 rounding of the boundary between them.
+ * Errors: NULL_ARG, BAD_SHAPE, BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
+ */
+size_t hippo_spec_verify_workspace_bytes(int32_t batch, int32_t gamma, int32_t vocab, int32_t dtype);
+int hippo_spec_verify(const void* p_logits, const void* q_logits, int32_t dtype,
+                      int64_t p_stride_row, int64_t q_stride_row,
+                      const int32_t* draft_tokens, const float* u_accept, const float* u_sample,
+                      int32_t batch, int32_t gamma, int32_t vocab, float temperature,
+                      int32_t* n_accept_out, int32_t* next_token_out, float* alpha_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

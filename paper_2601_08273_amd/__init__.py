@@ -19,7 +19,8 @@ SCORE_ATTN, SCORE_TEMP, SCORE_SPA, SCORE_ALL, SCORE_ACCUMULATE_ONLY = 1, 2, 4, 7
 OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = range(7)
 
 EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
-           "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention")
+           "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention",
+           "hippo_spec_verify_workspace_bytes", "hippo_spec_verify")
 
 
 class KvDesc(C.Structure):
@@ -64,6 +65,10 @@ def load():
     for fn in (lib.hippo_verify_attention, lib.hippo_draft_attention):
         fn.argtypes = [vp, i32, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
+    lib.hippo_spec_verify_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.hippo_spec_verify_workspace_bytes.restype = C.c_size_t
+    lib.hippo_spec_verify.argtypes = [vp, vp, i32, i64, i64, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, sz, vp]
+    lib.hippo_spec_verify.restype = C.c_int
     _lib = lib
     return lib
 
@@ -222,3 +227,38 @@ def hippo_draft_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: floa
                           want_lse: bool = False, out=None, workspace=None, stream=None):
     return _attention("hippo_draft_attention", CALL_DRAFT_ATTENTION, q, k_cache, v_cache, ctx_len,
                       softmax_scale, num_splits, want_lse, out, workspace, stream)
+
+
+def hippo_spec_verify(p_logits, q_logits, draft_tokens, u_accept, u_sample, temperature: float,
+                      want_alpha: bool = False, n_accept_out=None, next_token_out=None, workspace=None,
+                      stream=None):
+    """p_logits [B,gamma+1,V] (rows may be padded: stride(1) >= V), q_logits [B,gamma,V] or None
+    (greedy), draft_tokens [B,gamma] int32, u_accept [B,gamma] fp32, u_sample [B] fp32 ->
+    (n_accept [B] int32, next_token [B] int32[, alpha [B,gamma] fp32])."""
+    torch = _torch()
+    lib = load()
+    assert p_logits.dim() == 3 and p_logits.stride(2) == 1
+    B, g1, V = p_logits.shape
+    gamma = g1 - 1
+    assert p_logits.stride(0) == g1 * p_logits.stride(1)
+    q_stride = 0
+    if gamma == 0:
+        q_logits = draft_tokens = u_accept = None       # nothing to verify: a plain draw from p_0
+    if q_logits is not None:
+        assert q_logits.shape == (B, gamma, V) and q_logits.stride(2) == 1 and q_logits.dtype == p_logits.dtype
+        assert q_logits.stride(0) == gamma * q_logits.stride(1)
+        q_stride = q_logits.stride(1)
+    for t, dt in ((draft_tokens, torch.int32), (u_accept, torch.float32), (u_sample, torch.float32)):
+        assert t is None or (t.dtype == dt and t.is_contiguous())
+    dev = p_logits.device
+    n_acc = n_accept_out if n_accept_out is not None else torch.empty(B, dtype=torch.int32, device=dev)
+    nxt = next_token_out if next_token_out is not None else torch.empty(B, dtype=torch.int32, device=dev)
+    alpha = torch.empty((B, gamma), dtype=torch.float32, device=dev) if want_alpha else None
+    code = _dtype_code(p_logits)
+    ws = _workspace(int(lib.hippo_spec_verify_workspace_bytes(B, gamma, V, code)), dev, workspace)
+    st = lib.hippo_spec_verify(_ptr(p_logits), _ptr(q_logits), code, p_logits.stride(1), q_stride,
+                               _ptr(draft_tokens), _ptr(u_accept), _ptr(u_sample), B, gamma, V,
+                               float(temperature), _ptr(n_acc), _ptr(nxt), _ptr(alpha), _ptr(ws), ws.numel(),
+                               _stream(stream))
+    _check(st, "hippo_spec_verify")
+    return (n_acc, nxt, alpha) if want_alpha else (n_acc, nxt)

@@ -148,6 +148,26 @@ int check_crop(const hippo_video_desc* vid) {
   return HIPPO_OK;
 }
 
+// ---- speculative-sampling verification planning -------------------------------------------------
+struct SpecPlan {
+  int n_seg, n_rows;
+  size_t off_cells, off_chosen, bytes;
+};
+
+int plan_spec(int batch, int gamma, int vocab, int dtype, SpecPlan* pl) {
+  if (dtype != HIPPO_DTYPE_F32 && dtype != HIPPO_DTYPE_BF16) return HIPPO_ERR_BAD_DTYPE;
+  if (batch < 1 || batch > 65535 || gamma < 0 || gamma > kSdMaxGamma || vocab < 1 || vocab > kSdMaxVocab)
+    return HIPPO_ERR_BAD_SHAPE;
+  pl->n_seg = (vocab + kSdSeg - 1) / kSdSeg;
+  pl->n_rows = 2 * gamma + 1;
+  const size_t stats = align_up((size_t)batch * pl->n_rows * pl->n_seg * sizeof(SegStat), 256);
+  const size_t cells = align_up((size_t)batch * 2 * pl->n_seg * spec_cells_per_segment(dtype) * sizeof(float), 256);
+  pl->off_cells = stats;
+  pl->off_chosen = stats + cells;
+  pl->bytes = stats + cells + align_up((size_t)batch * sizeof(Chosen), 256);
+  return HIPPO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -290,6 +310,49 @@ int hippo_draft_attention(const void* q, int32_t q_len, const void* k_cache, con
                           void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
   return attention_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
                          num_splits, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+size_t hippo_spec_verify_workspace_bytes(int32_t batch, int32_t gamma, int32_t vocab, int32_t dtype) {
+  SpecPlan pl;
+  return plan_spec(batch, gamma, vocab, dtype, &pl) == HIPPO_OK ? pl.bytes : 0;
+}
+
+int hippo_spec_verify(const void* p_logits, const void* q_logits, int32_t dtype, int64_t p_stride_row,
+                      int64_t q_stride_row, const int32_t* draft_tokens, const float* u_accept,
+                      const float* u_sample, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
+                      int32_t* n_accept_out, int32_t* next_token_out, float* alpha_out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  SpecPlan pl;
+  int rc = plan_spec(batch, gamma, vocab, dtype, &pl);
+  if (rc != HIPPO_OK) return rc;
+  if (!(temperature >= 0.f) || isinf(temperature)) return HIPPO_ERR_BAD_SHAPE;
+  const bool greedy = temperature == 0.f;
+  if (p_logits == nullptr || n_accept_out == nullptr || next_token_out == nullptr || workspace == nullptr)
+    return HIPPO_ERR_NULL_ARG;
+  if (gamma > 0 && (draft_tokens == nullptr || (!greedy && (q_logits == nullptr || u_accept == nullptr))))
+    return HIPPO_ERR_NULL_ARG;
+  if (!greedy && u_sample == nullptr) return HIPPO_ERR_NULL_ARG;
+  if (p_stride_row < vocab || (gamma > 0 && !greedy && q_stride_row < vocab)) return HIPPO_ERR_BAD_SHAPE;
+  const int per16 = 16 / elem_bytes(dtype);
+  if (p_stride_row % per16 || !aligned16(p_logits) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return HIPPO_ERR_BAD_ALIGN;
+  if (gamma > 0 && !greedy && (q_stride_row % per16 || !aligned16(q_logits))) return HIPPO_ERR_BAD_ALIGN;
+  if (workspace_bytes < pl.bytes) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
+
+  SpecParams p;
+  p.p_logits = p_logits; p.q_logits = q_logits; p.tokens = draft_tokens;
+  p.u_accept = u_accept; p.u_sample = u_sample;
+  p.B = batch; p.gamma = gamma; p.V = vocab; p.n_rows = pl.n_rows; p.n_seg = pl.n_seg;
+  p.p_stride = p_stride_row; p.q_stride = q_stride_row;
+  p.c = greedy ? 0.f : kLog2e / temperature;
+  p.inv_temperature = greedy ? 0.0 : 1.0 / (double)temperature;
+  p.n_accept = n_accept_out; p.next_token = next_token_out; p.alpha_out = alpha_out;
+  char* ws = static_cast<char*>(workspace);
+  p.stats = reinterpret_cast<SegStat*>(ws);
+  p.cells = reinterpret_cast<float*>(ws + pl.off_cells);
+  p.chosen = reinterpret_cast<Chosen*>(ws + pl.off_chosen);
+  const hipError_t e = launch_spec_verify(p, dtype, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
 }
 
 }  // extern "C"

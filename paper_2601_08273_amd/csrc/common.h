@@ -129,4 +129,45 @@ struct SelectParams {
 };
 hipError_t launch_select_gather(const SelectParams& p, hipStream_t st);
 
+// ---- speculative-sampling verification ---------------------------------------------------------
+constexpr int kSdSeg = 8192;        // vocabulary entries handled by one block
+constexpr int kSdMaxGamma = 64;     // longest draft chain
+constexpr int kSdMaxVocab = 1 << 20;
+
+struct SegStat {   // statistics of one segment of one logits row
+  float m;         // maximum logit (-inf if the segment is all -inf)
+  float z;         // sum of exp2((x - m) * c) over the segment
+  int arg;         // index (in the row) of the first maximum
+  int pad;
+};
+struct Chosen {    // the row the next token is drawn from, and its normalisers
+  int row;         // first rejected position, or gamma after a full acceptance
+  int use_residual;
+  float mp, inv_zp, mq, inv_zq;
+  int pad0, pad1;
+};
+
+struct SpecParams {
+  const void* p_logits;      // [B, gamma+1, p_stride]
+  const void* q_logits;      // [B, gamma, q_stride]; unused when c == 0
+  const int32_t* tokens;     // [B, gamma]
+  const float* u_accept;     // [B, gamma]
+  const float* u_sample;     // [B]
+  int B, gamma, V;
+  int n_rows;                // 2*gamma + 1 (target rows, then draft rows)
+  int n_seg;                 // ceil(V / kSdSeg)
+  long long p_stride, q_stride;
+  float c;                   // log2(e) / temperature; 0 = greedy
+  double inv_temperature;
+  int32_t* n_accept;
+  int32_t* next_token;
+  float* alpha_out;          // may be null
+  // workspace pieces
+  SegStat* stats;            // [B, n_rows, n_seg]
+  float* cells;              // [B, 2 (p, residual), n_seg * cells_per_segment]
+  Chosen* chosen;            // [B]
+};
+hipError_t launch_spec_verify(const SpecParams& p, int dtype, hipStream_t st);
+int spec_cells_per_segment(int dtype);
+
 }  // namespace hippo

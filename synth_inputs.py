@@ -205,3 +205,19 @@ def random_scores(n_batch: int, n: int, seed: int, n_distinct: int = 0) -> np.nd
         vals = rng.standard_normal(n_distinct).astype(np.float32)
         return vals[rng.integers(0, n_distinct, size=(n_batch, n))]
     return rng.standard_normal((n_batch, n)).astype(np.float32)
+
+
+LM_VOCAB = 152064      # rows of the LM head of the 7B-class models the paper evaluates (Qwen2 family)
+
+
+def make_logits(n_batch: int, gamma: int, vocab: int, seed: int, closeness: float = 0.6):
+    """Target logits [B, gamma+1, V] and draft logits [B, gamma, V] for speculative-sampling
+    verification: an LM-head-like row (a few likely words far above a long Gaussian tail); the draft's
+    row is the target's plus noise of scale `closeness`, so acceptance is neither certain nor hopeless.
+    Returns (p_logits, q_logits, rng) -- the generator is handed back for the uniforms."""
+    rng = np.random.default_rng(seed)
+    pl = rng.standard_normal((n_batch, gamma + 1, vocab)).astype(np.float32) * 2.0
+    hot = rng.integers(0, vocab, (n_batch, gamma + 1, 4))
+    np.put_along_axis(pl, hot, pl.max() + rng.random((n_batch, gamma + 1, 4)).astype(np.float32) * 4.0, axis=-1)
+    ql = pl[:, :gamma] + closeness * rng.standard_normal((n_batch, gamma, vocab)).astype(np.float32)
+    return pl, ql, rng

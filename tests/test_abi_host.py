@@ -143,3 +143,35 @@ def test_binding_refuses_missing_library(monkeypatch, tmp_path):
     monkeypatch.setattr(h, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         h.load()
+
+
+def test_spec_verify_argument_errors(lib):
+    V, g = 151936, 5
+    need = lib.hippo_spec_verify_workspace_bytes(1, g, V, h.DTYPE_BF16)
+    assert need > 0 and need % 256 == 0
+    assert lib.hippo_spec_verify_workspace_bytes(1, g, V, 5) == 0
+    assert lib.hippo_spec_verify_workspace_bytes(1, 65, V, h.DTYPE_F32) == 0
+    assert lib.hippo_spec_verify_workspace_bytes(1, g, (1 << 20) + 1, h.DTYPE_F32) == 0
+
+    def call(p=FAKE, q=FAKE, dtype=h.DTYPE_BF16, ps=V, qs=V, tok=FAKE, ua=FAKE, us=FAKE, B=1, gamma=g, vocab=V,
+             T=1.0, nacc=FAKE, nxt=FAKE, ws=FAKE, ws_bytes=need):
+        return lib.hippo_spec_verify(p, q, dtype, ps, qs, tok, ua, us, B, gamma, vocab, T, nacc, nxt, None, ws,
+                                     ws_bytes, None)
+    assert call(p=None) == h.ERR_NULL_ARG
+    assert call(q=None) == h.ERR_NULL_ARG                       # sampling needs the draft's logits
+    assert call(tok=None) == h.ERR_NULL_ARG
+    assert call(us=None) == h.ERR_NULL_ARG
+    assert call(nxt=None) == h.ERR_NULL_ARG
+    assert call(ws=None) == h.ERR_NULL_ARG
+    assert call(dtype=2) == h.ERR_BAD_DTYPE
+    assert call(gamma=-1) == h.ERR_BAD_SHAPE
+    assert call(gamma=65) == h.ERR_BAD_SHAPE
+    assert call(vocab=0) == h.ERR_BAD_SHAPE
+    assert call(B=0) == h.ERR_BAD_SHAPE
+    assert call(T=-1.0) == h.ERR_BAD_SHAPE
+    assert call(T=float("nan")) == h.ERR_BAD_SHAPE
+    assert call(ps=V - 8) == h.ERR_BAD_SHAPE                    # rows overlap
+    assert call(ps=V + 4) == h.ERR_BAD_ALIGN                    # bf16 rows must stay 16-byte aligned
+    assert call(q=FAKE + 2) == h.ERR_BAD_ALIGN
+    assert call(ws=FAKE + 64) == h.ERR_BAD_ALIGN
+    assert call(ws_bytes=need - 1) == h.ERR_WORKSPACE_TOO_SMALL
