@@ -215,6 +215,87 @@ int hippo_spec_verify(const void* p_logits, const void* q_logits, int32_t dtype,
                       int32_t* n_accept_out, int32_t* next_token_out, float* alpha_out,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Host-side control of video parallel speculative decoding (Method, "Video Parallel Speculative
+ * Decoding").  No device work and no device pointers: every argument here is a HOST pointer.
+ *
+ * A round launches one target verification and, concurrently on another stream, draft decoding:
+ *   optimistic mode   (the previous batch was fully accepted, or a prefill buffer exists): the target
+ *                     verifies all n_pending buffered draft tokens while the draft model generates the
+ *                     next gamma.  Full acceptance emits the verified tokens and the new batch becomes
+ *                     the buffer (the extra token of serial speculative decoding is not taken: the draft
+ *                     has already continued past it).  A rejection emits the accepted prefix plus the
+ *                     target's replacement and discards every other draft; mode becomes conservative.
+ *   conservative mode (a rejection occurred, nothing buffered): the draft model generates x_1; then
+ *                     the target verifies x_1 alone while the draft generates x_2..x_gamma.  If x_1
+ *                     is rejected drafting is aborted, the replacement is emitted and the mode stays;
+ *                     if accepted, x_1 is emitted, x_2..x_gamma become the buffer and the mode becomes
+ *                     optimistic.
+ * (The paper fixes neither what happens to the extra token in the parallel modes nor how many
+ * buffered tokens one verification takes; the above is this library's reading.)
+ */
+enum hippo_vpsd_mode { HIPPO_VPSD_CONSERVATIVE = 0, HIPPO_VPSD_OPTIMISTIC = 1 };
+enum hippo_vpsd_policy { HIPPO_POLICY_AUTOREGRESSIVE = 0, HIPPO_POLICY_SERIAL_SD = 1, HIPPO_POLICY_VPSD = 2 };
+
+typedef struct hippo_vpsd_state {
+  int32_t gamma;            /* draft tokens per batch, 1..64 */
+  int32_t mode;             /* enum hippo_vpsd_mode */
+  int32_t n_pending;        /* drafted tokens waiting for verification */
+  int32_t reserved;
+  int64_t n_emitted;        /* tokens committed to the output so far */
+  int64_t n_rounds, n_target_calls;
+  int64_t n_draft_tokens;   /* draft forward passes so far (prefill buffer included) */
+  int64_t n_draft_wasted;   /* draft tokens generated and then discarded */
+  int64_t n_mode_switches;
+} hippo_vpsd_state;
+
+typedef struct hippo_vpsd_round {
+  int32_t mode;             /* the mode this round runs in */
+  int32_t draft_serial;     /* draft tokens to generate BEFORE the parallel phase (1 in conservative mode) */
+  int32_t verify_len;       /* draft tokens the target verifies: hippo_verify_attention q_len = verify_len + 1,
+                               hippo_spec_verify gamma = verify_len */
+  int32_t draft_parallel;   /* draft tokens to generate concurrently with that verification */
+} hippo_vpsd_round;
+
+typedef struct hippo_vpsd_result {
+  double time;              /* modelled wall time, in the unit of t_draft / t_target */
+  double speedup;           /* n_emitted * t_target / time: against one target forward per token */
+  int64_t n_emitted, n_rounds, n_target_calls, n_draft_tokens, n_draft_wasted, n_mode_switches;
+  int64_t n_flags_used;
+} hippo_vpsd_result;
+
+/* Tokens the draft model can decode while the target model is still in prefill ("Synchronous
+ * Draft-Target Prefill"): floor((t_prefill_target - t_prefill_draft) / t_draft_token), 0 if the
+ * target is not slower; the paper's example (0.8 s, 0.2 s, 50 ms) gives 12.  -1 on invalid times. */
+int32_t hippo_vpsd_prefill_buffer(double t_prefill_target, double t_prefill_draft, double t_draft_token);
+
+/* Start of generation: n_prefill_buffer (0..64) draft tokens already buffered; optimistic if any. */
+int hippo_vpsd_init(hippo_vpsd_state* state, int32_t gamma, int32_t n_prefill_buffer);
+/* What to enqueue in the next round.  Does not change the state. */
+int hippo_vpsd_plan(const hippo_vpsd_state* state, hippo_vpsd_round* round_out);
+/* Account for the round's outcome: n_accept in [0, verify_len] as hippo_spec_verify reports it,
+ * n_drafted_parallel = draft tokens actually produced concurrently (= draft_parallel unless
+ * drafting was cut short by a rejection).  Errors: NULL_ARG, BAD_SHAPE (a round that is not the
+ * one planned for this state, counts out of range, a fully accepted round whose new batch is
+ * incomplete). */
+int hippo_vpsd_commit(hippo_vpsd_state* state, const hippo_vpsd_round* round, int32_t n_accept,
+                      int32_t n_drafted_parallel);
+
+/* Timing model of a generation of at least n_tokens tokens under `policy`, with one draft forward
+ * costing t_draft, one target forward (any verify width: it is memory-bound) t_target, and the
+ * i-th verified draft token accepted iff accept[i] != 0 (flags beyond n_flags count as accepted;
+ * one flag is consumed per token looked at, the rejected one included).
+ *   AUTOREGRESSIVE: n_tokens target forwards.
+ *   SERIAL_SD: per round gamma draft forwards, then one verification; emits n_accept + 1 tokens
+ *     (Motivated Experiments, "Non-negligible Draft Latency": with t_target = 3 t_draft and gamma = 3
+ *     the speedup is 2 when everything is accepted and 0.5 when every first token is rejected).
+ *   VPSD: the state machine above; a fully accepted round costs draft_serial * t_draft +
+ *     max(t_target, draft_parallel * t_draft), a round with a rejection draft_serial * t_draft +
+ *     t_target (drafting is cut when the verdict arrives). */
+int hippo_vpsd_simulate(int32_t policy, int32_t gamma, double t_draft, double t_target,
+                        int32_t n_prefill_buffer, const uint8_t* accept, int64_t n_flags,
+                        int64_t n_tokens, hippo_vpsd_result* result_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,27 @@ OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO
 
 EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
            "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention",
-           "hippo_spec_verify_workspace_bytes", "hippo_spec_verify")
+           "hippo_spec_verify_workspace_bytes", "hippo_spec_verify", "hippo_vpsd_prefill_buffer",
+           "hippo_vpsd_init", "hippo_vpsd_plan", "hippo_vpsd_commit", "hippo_vpsd_simulate")
+VPSD_CONSERVATIVE, VPSD_OPTIMISTIC = 0, 1
+POLICY_AUTOREGRESSIVE, POLICY_SERIAL_SD, POLICY_VPSD = 0, 1, 2
+
+
+class VpsdState(C.Structure):
+    _fields_ = [("gamma", C.c_int32), ("mode", C.c_int32), ("n_pending", C.c_int32), ("reserved", C.c_int32),
+                ("n_emitted", C.c_int64), ("n_rounds", C.c_int64), ("n_target_calls", C.c_int64),
+                ("n_draft_tokens", C.c_int64), ("n_draft_wasted", C.c_int64), ("n_mode_switches", C.c_int64)]
+
+
+class VpsdRound(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("draft_serial", C.c_int32), ("verify_len", C.c_int32),
+                ("draft_parallel", C.c_int32)]
+
+
+class VpsdResult(C.Structure):
+    _fields_ = [("time", C.c_double), ("speedup", C.c_double), ("n_emitted", C.c_int64), ("n_rounds", C.c_int64),
+                ("n_target_calls", C.c_int64), ("n_draft_tokens", C.c_int64), ("n_draft_wasted", C.c_int64),
+                ("n_mode_switches", C.c_int64), ("n_flags_used", C.c_int64)]
 
 
 class KvDesc(C.Structure):
@@ -64,6 +84,15 @@ def load():
     lib.hippo_select_gather_kv.restype = C.c_int
     for fn in (lib.hippo_verify_attention, lib.hippo_draft_attention):
         fn.argtypes = [vp, i32, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
+        fn.restype = C.c_int
+    f64 = C.c_double
+    lib.hippo_vpsd_prefill_buffer.argtypes = [f64, f64, f64]
+    lib.hippo_vpsd_prefill_buffer.restype = C.c_int32
+    lib.hippo_vpsd_init.argtypes = [C.POINTER(VpsdState), i32, i32]
+    lib.hippo_vpsd_plan.argtypes = [C.POINTER(VpsdState), C.POINTER(VpsdRound)]
+    lib.hippo_vpsd_commit.argtypes = [C.POINTER(VpsdState), C.POINTER(VpsdRound), i32, i32]
+    lib.hippo_vpsd_simulate.argtypes = [i32, i32, f64, f64, i32, vp, i64, i64, C.POINTER(VpsdResult)]
+    for fn in (lib.hippo_vpsd_init, lib.hippo_vpsd_plan, lib.hippo_vpsd_commit, lib.hippo_vpsd_simulate):
         fn.restype = C.c_int
     lib.hippo_spec_verify_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.hippo_spec_verify_workspace_bytes.restype = C.c_size_t
@@ -240,13 +269,13 @@ def hippo_spec_verify(p_logits, q_logits, draft_tokens, u_accept, u_sample, temp
     assert p_logits.dim() == 3 and p_logits.stride(2) == 1
     B, g1, V = p_logits.shape
     gamma = g1 - 1
-    assert p_logits.stride(0) == g1 * p_logits.stride(1)
+    assert B == 1 or p_logits.stride(0) == g1 * p_logits.stride(1)
     q_stride = 0
     if gamma == 0:
         q_logits = draft_tokens = u_accept = None       # nothing to verify: a plain draw from p_0
     if q_logits is not None:
         assert q_logits.shape == (B, gamma, V) and q_logits.stride(2) == 1 and q_logits.dtype == p_logits.dtype
-        assert q_logits.stride(0) == gamma * q_logits.stride(1)
+        assert B == 1 or q_logits.stride(0) == gamma * q_logits.stride(1)
         q_stride = q_logits.stride(1)
     for t, dt in ((draft_tokens, torch.int32), (u_accept, torch.float32), (u_sample, torch.float32)):
         assert t is None or (t.dtype == dt and t.is_contiguous())
@@ -262,3 +291,39 @@ def hippo_spec_verify(p_logits, q_logits, draft_tokens, u_accept, u_sample, temp
                                _stream(stream))
     _check(st, "hippo_spec_verify")
     return (n_acc, nxt, alpha) if want_alpha else (n_acc, nxt)
+
+
+# ---------------------------------------------------------------------------------------------
+# host-side control of video parallel speculative decoding (no GPU involved)
+# ---------------------------------------------------------------------------------------------
+
+def vpsd_prefill_buffer(t_prefill_target: float, t_prefill_draft: float, t_draft_token: float) -> int:
+    return int(load().hippo_vpsd_prefill_buffer(t_prefill_target, t_prefill_draft, t_draft_token))
+
+
+def vpsd_init(gamma: int, n_prefill_buffer: int = 0) -> VpsdState:
+    s = VpsdState()
+    _check(load().hippo_vpsd_init(C.byref(s), gamma, n_prefill_buffer), "hippo_vpsd_init")
+    return s
+
+
+def vpsd_plan(state: VpsdState) -> VpsdRound:
+    r = VpsdRound()
+    _check(load().hippo_vpsd_plan(C.byref(state), C.byref(r)), "hippo_vpsd_plan")
+    return r
+
+
+def vpsd_commit(state: VpsdState, rnd: VpsdRound, n_accept: int, n_drafted_parallel: Optional[int] = None) -> None:
+    n = rnd.draft_parallel if n_drafted_parallel is None else n_drafted_parallel
+    _check(load().hippo_vpsd_commit(C.byref(state), C.byref(rnd), n_accept, n), "hippo_vpsd_commit")
+
+
+def vpsd_simulate(policy: int, gamma: int, t_draft: float, t_target: float, accept, n_tokens: int,
+                  n_prefill_buffer: int = 0) -> VpsdResult:
+    flags = bytes(bytearray(1 if a else 0 for a in accept))
+    res = VpsdResult()
+    buf = C.create_string_buffer(flags, len(flags)) if flags else None
+    _check(load().hippo_vpsd_simulate(policy, gamma, t_draft, t_target, n_prefill_buffer,
+                                      C.cast(buf, C.c_void_p) if buf is not None else None, len(flags), n_tokens,
+                                      C.byref(res)), "hippo_vpsd_simulate")
+    return res

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhippo.so")
-SOURCES = ["api.hip", "attention.hip", "score.hip", "select_gather.hip", "spec_verify.hip"]
+SOURCES = ["api.hip", "attention.hip", "score.hip", "select_gather.hip", "spec_verify.hip", "vpsd.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instruction forms
@@ -25,8 +25,9 @@ FLAGS = [
 
 
 def _compile(src: str, extra) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    cmd = ["hipcc", *FLAGS, *extra, *(["-x", "hip"] if src.endswith(".cpp") else []), "-c", os.path.join(CSRC, src),
+           "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "not a recognized feature" not in l)
     if r.returncode != 0:
