@@ -140,10 +140,16 @@ __global__ __launch_bounds__(kSdThreads) void sd_cells(SpecParams p) {
 
   // the few dependent loads first, so they overlap the statistics fetch
   int x = 0;
-  float u = 0.f;
+  float u = 0.f, lp_raw = 0.f, lq_raw = 0.f;
   if (tid < p.gamma) {
     x = p.tokens[(long long)b * p.gamma + tid];
-    if (!greedy) u = p.u_accept[(long long)b * p.gamma + tid];
+    if (!greedy) {
+      u = p.u_accept[(long long)b * p.gamma + tid];
+      if (x >= 0 && x < p.V) {
+        lp_raw = Elem<T>::load(pl + (long long)tid * p.p_stride + x);
+        lq_raw = Elem<T>::load(ql + (long long)tid * p.q_stride + x);
+      }
+    }
   }
   // segment statistics of every row of this sequence: one parallel fetch into LDS when they fit
   const int n_stats = (greedy ? p.gamma + 1 : p.n_rows) * p.n_seg;
@@ -171,8 +177,8 @@ __global__ __launch_bounds__(kSdThreads) void sd_cells(SpecParams p) {
       } else if (greedy) {
         alpha = (x == a) ? 1.0 : 0.0;
       } else {
-        const double lp = (double)Elem<T>::load(pl + (long long)tid * p.p_stride + x) - (double)m;
-        const double lq = (double)Elem<T>::load(ql + (long long)tid * p.q_stride + x) - (double)mq;
+        const double lp = (double)lp_raw - (double)m;
+        const double lq = (double)lq_raw - (double)mq;
         // p[x] / q[x] = exp((lp - lq) / T) * zq / zp;  p[x] = 0 -> 0;  q[x] = 0 -> p >= q -> 1
         if (lp == -INFINITY) alpha = (lq == -INFINITY) ? 1.0 : 0.0;
         else if (lq == -INFINITY) alpha = 1.0;
