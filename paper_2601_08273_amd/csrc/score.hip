@@ -117,23 +117,34 @@ constexpr int kSaMfmaTile = 256;      // tokens per block
 constexpr int kSaWaves = 8;           // waves per block, 32 tokens each: two waves per SIMD overlap MFMA and exp
 
 template <int D, int PASS>
-__global__ __launch_bounds__(kSaWaves * 64) void sattn_mfma(ScoreParams p) {
+struct SattnSmem {
+  static constexpr int RCH = 64;                 // query rows per LDS chunk
+  static constexpr int ROWB = D * 2 + 16;
+  static constexpr int RDEF = 512;               // pass 1 merges the waves' row statistics every RDEF rows
+  __align__(16) unsigned char Qs[RCH * ROWB];
+  float lse_s[RCH];
+  float wm_s[PASS == 1 ? kSaWaves : 1][PASS == 1 ? RDEF : 1];
+  float wl_s[PASS == 1 ? kSaWaves : 1][PASS == 1 ? RDEF : 1];
+};
+
+template <int D, int PASS>
+__device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<D, PASS>& sm, const int tile,
+                                                const int hk, const int b) {
   constexpr int NW = kSaWaves, NT = NW * 64;
   constexpr int TPW = kSaMfmaTile / NW;   // tokens per wave
   constexpr int TBW = TPW / 16;           // 16-token blocks per wave
   constexpr int KS = D / 32;
-  constexpr int ROWB = D * 2 + 16;
+  constexpr int ROWB = SattnSmem<D, PASS>::ROWB;
   constexpr int CPR = D / 8;
-  constexpr int RCH = 64;               // query rows per LDS chunk
-  __shared__ __align__(16) unsigned char Qs[RCH * ROWB];
-  __shared__ float lse_s[RCH];
-  constexpr int RDEF = 512;             // pass 1 merges the waves' row statistics every RDEF rows
-  __shared__ float wm_s[PASS == 1 ? NW : 1][PASS == 1 ? RDEF : 1];
-  __shared__ float wl_s[PASS == 1 ? NW : 1][PASS == 1 ? RDEF : 1];
+  constexpr int RCH = SattnSmem<D, PASS>::RCH;
+  constexpr int RDEF = SattnSmem<D, PASS>::RDEF;
+  unsigned char* Qs = sm.Qs;
+  float* lse_s = sm.lse_s;
+  auto& wm_s = sm.wm_s;
+  auto& wl_s = sm.wl_s;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
-  const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
   const int n0 = tile * kSaMfmaTile + wave * TPW;    // first token of this wave
   const int Rs = p.L * p.G;
   const float scale_log2 = rsqrtf((float)D) * kLog2e;
@@ -278,6 +289,12 @@ __global__ __launch_bounds__(kSaWaves * 64) void sattn_mfma(ScoreParams p) {
           p.col_part[((long long)b * p.Hkv + hk) * p.Nv + n0 + tb * 16 + 4 * g + e] = v;
       }
   }
+}
+
+template <int D, int PASS>
+__global__ __launch_bounds__(kSaWaves * 64) void sattn_mfma(ScoreParams p) {
+  __shared__ SattnSmem<D, PASS> sm;
+  sattn_mfma_body<D, PASS>(p, sm, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // merge the per-tile row statistics: lse2 = m* + log2(sum_t l_t 2^(m_t - m*)); one wave per row
@@ -584,24 +601,37 @@ __global__ __launch_bounds__(256) void emb_scores_mfma(ScoreParams p) {
 // neighbour frames between them (waves 0,1: Gram and previous frame; waves 2,3: next frame), so an
 // operand is fetched at most twice per block; the two channel halves are summed through LDS.
 // =================================================================================================
-__global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
-  constexpr int MP = 32;
+struct Emb32Smem {
+  static constexpr int MP = 32;
   // blocks: Gram (0,0) (0,1) (1,1); then for prev and for next: dot rb0, dot rb1, norm rb0, norm rb1
-  constexpr int NBLK = 11;
-  __shared__ f32x4 red[2][NBLK][64];                // partial blocks of the two channel halves
-  __shared__ float G[MP][MP + 1];
-  __shared__ float tdot[4][MP];
-  __shared__ float inv_norm[MP];
-  __shared__ int tok_s[MP];
+  static constexpr int NBLK = 11;
+  f32x4 red[2][NBLK][64];                           // partial blocks of the two channel halves
+  float G[MP][MP + 1];
+  float tdot[4][MP];
+  float inv_norm[MP];
+  int tok_s[MP];
+};
 
-  const int tid = threadIdx.x, lane = tid & 63;
+// One crop, computed by the 256 threads `tid` = 0..255 of a group; every thread of the block must
+// call it (it contains block-wide barriers).  BATCH = channel steps whose operands are in flight.
+template <int BATCH>
+__device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem& sm, const int tid,
+                                                const int crop_in_frame, const int f, const int b) {
+  constexpr int MP = Emb32Smem::MP;
+  constexpr int NBLK = Emb32Smem::NBLK;
+  auto& red = sm.red;
+  auto& G = sm.G;
+  auto& tdot = sm.tdot;
+  auto& inv_norm = sm.inv_norm;
+  auto& tok_s = sm.tok_s;
+
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int cg = wave & 1;                          // channel half: channel steps cg, cg+2, ...
   const int ig = wave >> 1;                         // 0: Gram + previous frame, 1: next frame
   const int j = lane & 15, g = lane >> 4;
   const int ncx = (p.gw + p.cw - 1) / p.cw;
-  const int cy = blockIdx.x / ncx, cx = blockIdx.x % ncx;
-  const int f = blockIdx.y, b = blockIdx.z;
+  const int cy = crop_in_frame / ncx, cx = crop_in_frame % ncx;
   const int y0 = cy * p.ch, x0 = cx * p.cw;
   const int mh = min(p.ch, p.gh - y0), mw = min(p.cw, p.gw - x0);
   const int M = mh * mw;
@@ -634,17 +664,17 @@ __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
   f32x4 acc[7];   // ig 0: Gram x3, dot x2, norm x2;  ig 1: (unused x3), dot x2, norm x2
 #pragma unroll
   for (int i = 0; i < 7; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  for (int ks0 = cg; ks0 < n_ks; ks0 += 8) {        // 4 channel steps of this wave per round
-    bf16x8 cur[4][2], nb[4][2];
+  for (int ks0 = cg; ks0 < n_ks; ks0 += 2 * BATCH) {   // BATCH channel steps of this wave per round
+    bf16x8 cur[BATCH][2], nb[BATCH][2];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < BATCH; ++u)
 #pragma unroll
       for (int rbk = 0; rbk < 2; ++rbk) {
         cur[u][rbk] = operand(0, rbk, ks0 + 2 * u);
         nb[u][rbk] = operand(dnb, rbk, ks0 + 2 * u);
       }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < BATCH; ++u) {
       if (ig == 0) {
         acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][0], acc[0], 0, 0, 0);
         acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[u][0], cur[u][1], acc[1], 0, 0, 0);
@@ -712,6 +742,39 @@ __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
     }
     p.s_temp[o] = 1.f - (cnt ? sum / (float)cnt : 0.f);
   }
+}
+
+__global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
+  __shared__ Emb32Smem sm;
+  emb_mfma32_body<4>(p, sm, threadIdx.x, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Pass 1 of s_attn and the embedding terms in ONE launch: the first n_sattn blocks run the
+// (compute-bound, one block per compute unit) row-statistics sweep, the remaining blocks run two
+// crops each and fill the second block slot of every compute unit, so the memory-bound embedding
+// work hides under the sweep instead of following it.  Two blocks fit a compute unit: 8 waves of
+// at most 128 registers each and the larger of the two shared-memory layouts.
+template <int D>
+__global__ __launch_bounds__(kSaWaves * 64, 4) void sattn_pass1_with_emb(ScoreParams p, int n_sattn) {
+  union Smem {
+    SattnSmem<D, 1> sa;
+    Emb32Smem emb[2];
+  };
+  __shared__ Smem sm;
+  const int blk = blockIdx.x;
+  if (blk < n_sattn) {
+    const int tile = blk % p.n_tile, rest = blk / p.n_tile;
+    sattn_mfma_body<D, 1>(p, sm.sa, tile, rest % p.Hkv, rest / p.Hkv);
+    return;
+  }
+  const int ncf = ((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw);   // crops per frame
+  const long long n_crops = (long long)ncf * p.F * p.B;
+  const int half = threadIdx.x >> 8;
+  long long crop = 2ll * (blk - n_sattn) + half;
+  if (crop >= n_crops) crop = n_crops - 1;       // odd count: the idle half repeats the last crop
+  const int c = (int)(crop % ncf);
+  const long long fb = crop / ncf;
+  emb_mfma32_body<2>(p, sm.emb[half], threadIdx.x & 255, c, (int)(fb % p.F), (int)(fb / p.F));
 }
 
 // =================================================================================================
@@ -792,9 +855,16 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
 }
 
 template <int D>
-static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st) {
+static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st, bool with_emb) {
   dim3 grid(p.n_tile, p.Hkv, p.B);
-  hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(kSaWaves * 64), 0, st, p);
+  if (with_emb) {
+    const long long n_sattn = (long long)p.n_tile * p.Hkv * p.B;
+    const long long n_crops = (long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B;
+    hipLaunchKernelGGL((sattn_pass1_with_emb<D>), dim3((unsigned)(n_sattn + (n_crops + 1) / 2)),
+                       dim3(kSaWaves * 64), 0, st, p, (int)n_sattn);
+  } else {
+    hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(kSaWaves * 64), 0, st, p);
+  }
   const long long rows = (long long)p.B * p.H * p.L;
   hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p);
   hipLaunchKernelGGL((sattn_mfma<D, 2>), grid, dim3(kSaWaves * 64), 0, st, p);
@@ -804,9 +874,15 @@ static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st) {
 hipError_t launch_score(const ScoreParams& p, hipStream_t st) {
   hipError_t e = hipSuccess;
   const bool accumulate_only = (p.flags & HIPPO_SCORE_ACCUMULATE_ONLY) != 0;
+  // bf16 with the paper's small crops: the embedding terms ride in the launch of s_attn's pass 1
+  const bool want_emb = (p.flags & (HIPPO_SCORE_TEMP | HIPPO_SCORE_SPA)) != 0;
+  const long long fused_blocks = (long long)p.n_tile * p.Hkv * p.B +
+      ((long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B + 1) / 2;
+  const bool emb_rides = want_emb && !accumulate_only && (p.flags & HIPPO_SCORE_ATTN) &&
+                         p.dtype == HIPPO_DTYPE_BF16 && p.ch * p.cw <= 32 && fused_blocks < (1ll << 31);
   if ((p.flags & HIPPO_SCORE_ATTN) || accumulate_only) {
     if (p.dtype == HIPPO_DTYPE_BF16)
-      e = (p.D == 128) ? launch_sattn_mfma<128>(p, st) : launch_sattn_mfma<64>(p, st);
+      e = (p.D == 128) ? launch_sattn_mfma<128>(p, st, emb_rides) : launch_sattn_mfma<64>(p, st, emb_rides);
     else
       e = (p.D == 128) ? launch_sattn_valu<float, 128>(p, st) : launch_sattn_valu<float, 64>(p, st);
     if (e != hipSuccess) return e;
@@ -816,7 +892,7 @@ hipError_t launch_score(const ScoreParams& p, hipStream_t st) {
       return hipGetLastError();
     }
   }
-  if (p.flags & (HIPPO_SCORE_TEMP | HIPPO_SCORE_SPA)) {
+  if (want_emb && !emb_rides) {
     const int ncy = (p.gh + p.ch - 1) / p.ch, ncx = (p.gw + p.cw - 1) / p.cw;
     dim3 grid(ncy * ncx, p.F, p.B);
     if (p.dtype == HIPPO_DTYPE_BF16) {
