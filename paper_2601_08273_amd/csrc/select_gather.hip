@@ -8,13 +8,30 @@
 // variation.
 #include "common.h"
 
+// Phase timestamps for tuning runs only (-DHIPPO_TRACE): thread 0 of block 0 records the cycle
+// counter at a few points and stores them at the end; compiled out of the library.
+#ifdef HIPPO_TRACE
+__device__ long long g_topk_trace[16];
+#define TOPK_TP_DECL long long tp_[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#define TOPK_TP(i_) tp_[i_] = (long long)wall_clock64();
+#define TOPK_TP_FLUSH                                              \
+  if (threadIdx.x == 0 && blockIdx.x == 0) {                       \
+    for (int i_ = 0; i_ < 10; ++i_) g_topk_trace[i_] = tp_[i_];    \
+  }
+#else
+#define TOPK_TP_DECL
+#define TOPK_TP(i_)
+#define TOPK_TP_FLUSH
+#endif
+
 namespace hippo {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kKeysPerThread = 40;       // keys held in registers: sequences up to 40960 tokens
 constexpr int kBins = 4096;              // 12-bit digits (the last pass uses 256 of them)
-constexpr int kBinsPerThread = kBins / kSelThreads;
+constexpr int kHistStride = kBins + kBins / 64;   // padded histogram
+__device__ __forceinline__ int hist_slot(int bin) { return bin + (bin >> 6); }
 
 // larger score -> larger key; -0 == +0; NaN -> 0, below every number (-inf maps to 0x007fffff)
 __device__ __forceinline__ uint32_t score_key(float x) {
@@ -24,20 +41,49 @@ __device__ __forceinline__ uint32_t score_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// inclusive scan over the 1024 threads of the block (wave scan, then the 16 wave totals)
-__device__ __forceinline__ unsigned block_incl_scan(unsigned v, unsigned* wave_tot) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// One wave walks a histogram from the top bin down (no barriers inside): lane l owns the BPL bins
+// below nb - 1 - BPL*l, read BATCH at a time so the LDS reads pipeline; an inclusive wave scan of
+// the lane sums counts the keys in all higher bins; the lane in which the running count reaches
+// `need` walks its bins again and publishes the digit and what is still needed inside it.
+template <int BPL, int BATCH>
+__device__ __forceinline__ void walk_histogram(const unsigned* h, int nb, int lane, unsigned prefix, unsigned need,
+                                               int shift, unsigned* out_prefix, unsigned* out_need) {
+  const int top = nb - 1 - BPL * lane;
+  unsigned hsum = 0;
+#pragma unroll 1
+  for (int q0 = 0; q0 < BPL; q0 += BATCH) {
+    unsigned v[BATCH];
+#pragma unroll
+    for (int q = 0; q < BATCH; ++q) v[q] = h[hist_slot(top - q0 - q)];
+#pragma unroll
+    for (int q = 0; q < BATCH; ++q) hsum += v[q];
+  }
+  unsigned incl = hsum;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    const unsigned n = __shfl_up(v, o, 64);
-    if (lane >= o) v += n;
+    const unsigned n = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += n;
   }
-  __syncthreads();
-  if (lane == 63) wave_tot[wave] = v;
-  __syncthreads();
-  unsigned off = 0;
-  for (int w = 0; w < wave; ++w) off += wave_tot[w];
-  return v + off;
+  unsigned above = incl - hsum;                 // keys in bins above this lane's
+  if (above < need && incl >= need) {           // exactly one lane
+    int d = top;
+    bool found = false;
+#pragma unroll 1
+    for (int q0 = 0; q0 < BPL; q0 += BATCH) {
+      unsigned v[BATCH];
+#pragma unroll
+      for (int q = 0; q < BATCH; ++q) v[q] = h[hist_slot(top - q0 - q)];
+#pragma unroll
+      for (int q = 0; q < BATCH; ++q) {
+        if (!found) {
+          if (above + v[q] >= need) { found = true; d = top - q0 - q; }
+          else above += v[q];
+        }
+      }
+    }
+    *out_prefix = prefix | ((unsigned)d << shift);
+    *out_need = need - above;
+  }
 }
 
 // One block per sequence.  NC > 0: every thread keeps its keys (index c*1024 + tid, c < NC) in
@@ -50,8 +96,10 @@ __device__ __forceinline__ unsigned block_incl_scan(unsigned v, unsigned* wave_t
 template <int NC>
 __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   constexpr bool CACHED = NC > 0;
-  __shared__ unsigned hist[kBins];
-  __shared__ unsigned wave_tot[kSelWaves];
+  // one histogram per radix pass (12, 12, 8 bits); bin i lives at i + i/64, so that the 64 lanes of
+  // the scanning wave, which own runs of 64 consecutive bins, hit different LDS banks
+  __shared__ unsigned hist[2 * kHistStride + 256 + 4];
+  __shared__ unsigned wave_tot[2][kSelWaves];
   __shared__ unsigned sh_prefix, sh_need;
 
   const int b = blockIdx.x, tid = threadIdx.x;
@@ -60,6 +108,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   int32_t* out = p.idx_out + (long long)b * p.k;
   const int n_chunks = (p.Nv + kSelThreads - 1) / kSelThreads;
 
+  TOPK_TP_DECL
+  TOPK_TP(0)
   unsigned keys[CACHED ? NC : 1];
   if (CACHED) {
 #pragma unroll
@@ -72,49 +122,74 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     return CACHED ? keys[c] : score_key(sc[c * kSelThreads + tid]);
   };
 
+  TOPK_TP(1)
   // ---- radix select of the k-th largest key ----
   unsigned prefix = 0, need = (unsigned)p.k;   // `need` keys still wanted among those matching prefix
   const int shifts[3] = {20, 8, 0};
   const unsigned masks[3] = {0u, 0xfff00000u, 0xffffff00u};   // bits already decided
   const unsigned dmask[3] = {0xfffu, 0xfffu, 0xffu};
+  // the three histograms are cleared once, up front
+  for (int i = tid; i < 2 * kHistStride + 256 + 4; i += kSelThreads) hist[i] = 0;
+  __syncthreads();
 #pragma unroll
   for (int pass = 0; pass < 3; ++pass) {
-    for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
-    __syncthreads();
+    unsigned* h = hist + (pass == 0 ? 0 : pass == 1 ? kHistStride : 2 * kHistStride);
     if (CACHED) {
 #pragma unroll
       for (int c = 0; c < NC; ++c)
         if (c < n_chunks && c * kSelThreads + tid < p.Nv && (keys[c] & masks[pass]) == prefix)
-          atomicAdd(&hist[(keys[c] >> shifts[pass]) & dmask[pass]], 1u);
+          atomicAdd(&h[hist_slot((keys[c] >> shifts[pass]) & dmask[pass])], 1u);
     } else {
       for (int c = 0; c < n_chunks; ++c)
         if (c * kSelThreads + tid < p.Nv) {
           const unsigned key = key_at(c);
-          if ((key & masks[pass]) == prefix) atomicAdd(&hist[(key >> shifts[pass]) & dmask[pass]], 1u);
+          if ((key & masks[pass]) == prefix) atomicAdd(&h[hist_slot((key >> shifts[pass]) & dmask[pass])], 1u);
         }
     }
     __syncthreads();
-    // thread t looks at its kBinsPerThread bins from the top down, thread 0 holding the highest:
-    // an inclusive scan over t then counts the keys in all higher bins
-    const int top = kBins - 1 - kBinsPerThread * tid;
-    unsigned hsum = 0;
+    if (pass == 2) {
+      if (wave == 0) walk_histogram<4, 4>(h, 256, lane, prefix, need, shifts[pass], &sh_prefix, &sh_need);
+    } else {
+      // all threads: thread t sums its 4 bins from the top down (thread 0 holds the highest), a block
+      // scan counts the keys in all higher bins, and the one thread in which the running count reaches
+      // `need` walks its bins again
+      constexpr int BPT = kBins / kSelThreads;
+      const int top = kBins - 1 - BPT * tid;
+      unsigned hv[BPT], hsum = 0;
 #pragma unroll
-    for (int q = 0; q < kBinsPerThread; ++q) hsum += hist[top - q];
-    const unsigned incl = block_incl_scan(hsum, wave_tot);
-    unsigned above = incl - hsum;                         // keys in bins above this thread's
-    if (above < need && incl >= need) {                   // exactly one thread
-      unsigned d = top;
+      for (int q = 0; q < BPT; ++q) { hv[q] = h[hist_slot(top - q)]; hsum += hv[q]; }
+      unsigned incl = hsum;
 #pragma unroll
-      for (int q = 0; q < kBinsPerThread - 1; ++q) {
-        const unsigned hh = hist[top - q];
-        if (d == (unsigned)(top - q) && above + hh < need) { above += hh; d = top - q - 1; }
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned n = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += n;
       }
-      sh_prefix = prefix | (d << shifts[pass]);
-      sh_need = need - above;
+      if (lane == 63) wave_tot[pass][wave] = incl;
+      __syncthreads();
+      unsigned tot[kSelWaves];
+#pragma unroll
+      for (int w = 0; w < kSelWaves; ++w) tot[w] = wave_tot[pass][w];     // independent reads, one wait
+#pragma unroll
+      for (int w = 0; w < kSelWaves; ++w) incl += (w < wave) ? tot[w] : 0u;
+      unsigned above = incl - hsum;
+      if (above < need && incl >= need) {                   // exactly one thread
+        int d = top;
+        bool found = false;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+          if (!found) {
+            if (above + hv[q] >= need) { found = true; d = top - q; }
+            else above += hv[q];
+          }
+        }
+        sh_prefix = prefix | ((unsigned)d << shifts[pass]);
+        sh_need = need - above;
+      }
     }
     __syncthreads();
     prefix = sh_prefix;
     need = sh_need;
+    TOPK_TP(2 + pass)
   }
   const unsigned thr = prefix;      // the k-th largest key
   const unsigned need_eq = need;    // how many keys equal to it are kept (lowest indices first)
@@ -122,7 +197,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   // ---- compaction in index order ----
   // counts per (chunk, wave) in chunk-major order reuse the histogram storage: [2][n_chunks*16]
   unsigned* cnt_gt = hist;
-  unsigned* cnt_eq = hist + kKeysPerThread * kSelWaves;
+  unsigned* cnt_eq = hist + kKeysPerThread * kSelWaves;     // 2 x 640 entries, well inside hist
   __syncthreads();
   auto flags = [&](int c, bool& gt, bool& eq) {
     gt = eq = false;
@@ -143,23 +218,38 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
       }
     }
     __syncthreads();
-    // exclusive scan of both count arrays in (chunk, wave) order; n_chunks * waves <= 640 entries,
-    // handled kSelThreads at a time with a running carry
-    const int n_ent = n_chunks * kSelWaves;
-    unsigned carry_g = 0, carry_e = 0;
-    for (int e0 = 0; e0 < n_ent; e0 += kSelThreads) {
-      const int e = e0 + tid;
-      const unsigned vg = e < n_ent ? cnt_gt[e] : 0u, ve = e < n_ent ? cnt_eq[e] : 0u;
-      const unsigned ig = block_incl_scan(vg, wave_tot);
-      const unsigned ie = block_incl_scan(ve, wave_tot);
-      __syncthreads();
-      if (e < n_ent) { cnt_gt[e] = carry_g + ig - vg; cnt_eq[e] = carry_e + ie - ve; }
-      if (tid == kSelThreads - 1) { sh_prefix = ig; sh_need = ie; }
-      __syncthreads();
-      carry_g += sh_prefix;
-      carry_e += sh_need;
-      __syncthreads();
+    TOPK_TP(5)
+    // exclusive scan of both count arrays in (chunk, wave) order, by one wave: n_chunks * waves
+    // <= 640 entries, up to 10 consecutive ones per lane, read in one batch
+    if (wave == 0) {
+      const int n_ent = n_chunks * kSelWaves;
+      constexpr int EPL = (kKeysPerThread * kSelWaves + 63) / 64;       // entries per lane
+      unsigned sg = 0, se = 0;
+#pragma unroll
+      for (int q = 0; q < EPL; ++q) {
+        const int e = lane * EPL + q;
+        sg += e < n_ent ? cnt_gt[e] : 0u;
+        se += e < n_ent ? cnt_eq[e] : 0u;
+      }
+      unsigned ig = sg, ie = se;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned ng = __shfl_up(ig, o, 64), ne = __shfl_up(ie, o, 64);
+        if (lane >= o) { ig += ng; ie += ne; }
+      }
+      unsigned rg = ig - sg, re = ie - se;
+#pragma unroll
+      for (int q = 0; q < EPL; ++q) {               // a lane rewrites only its own entries
+        const int e = lane * EPL + q;
+        if (e < n_ent) {
+          const unsigned g0 = cnt_gt[e], e0 = cnt_eq[e];
+          cnt_gt[e] = rg; cnt_eq[e] = re;
+          rg += g0; re += e0;
+        }
+      }
     }
+    __syncthreads();
+    TOPK_TP(6)
     const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -197,6 +287,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
       __syncthreads();
     }
   }
+  TOPK_TP(7)
+  TOPK_TP_FLUSH
 }
 
 // dst row n of (b, hk): n < vis_off -> src n ; n < vis_off + k -> src vis_off + idx[n - vis_off] ;
