@@ -103,9 +103,9 @@ struct ScoreParams {
   float* scores_out;
   float* components_out;
   // workspace pieces
-  float* row_m;      // [B, H, L, n_tile] partial row maxima
-  float* row_l;      // [B, H, L, n_tile] partial row sums
-  float* row_lse;    // [B, H, L] final log2-domain row normaliser
+  float* row_m;      // [n_tile, B, Hkv, L*G] partial row maxima (row r = i*G + g of a KV head)
+  float* row_l;      // [n_tile, B, Hkv, L*G] partial row sums
+  float* row_lse;    // [B, Hkv, L*G] final log2-domain row normaliser
   float* col_part;   // [B, Hkv, Nv] per-KV-head column sums
   float* s_attn;     // [B, Nv]
   float* s_temp;     // [B, Nv]

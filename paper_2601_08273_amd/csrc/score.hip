@@ -18,6 +18,13 @@ namespace hippo {
 // =================================================================================================
 constexpr int kSaValuTile = 32;
 
+// Where pass 1 leaves the (max, sum) of query row r = i*G + g of KV head hk for token tile `tile`:
+// tile-major slabs of all B*H*L rows in (b, hk, r) order, so a block writes consecutive floats and
+// the merge reads consecutive rows.  row_lse uses the same (b, hk, r) order.
+__device__ __forceinline__ long long sattn_part_at(const ScoreParams& p, int tile, int b, int hk, int r) {
+  return (long long)tile * ((long long)p.B * p.H * p.L) + ((long long)b * p.Hkv + hk) * ((long long)p.L * p.G) + r;
+}
+
 template <typename T, int D, int PASS>
 __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
   constexpr int TT = kSaValuTile, RC = 32;
@@ -65,7 +72,7 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
     if (PASS == 2 && tid < RC) {
       const int r = r0 + tid;
       float v = INFINITY;   // padding rows contribute exp2(-inf) = 0
-      if (r < Rs) v = p.row_lse[((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G];
+      if (r < Rs) v = p.row_lse[((long long)b * p.Hkv + hk) * Rs + r];
       lse_s[tid] = v;
     }
     __syncthreads();
@@ -87,9 +94,9 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
         if (tok == 0 && r < Rs) {
-          const long long row = ((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G;
-          p.row_m[row * p.n_tile + tile] = mx;
-          p.row_l[row * p.n_tile + tile] = ps;
+          const long long at = sattn_part_at(p, tile, b, hk, r);
+          p.row_m[at] = mx;
+          p.row_l[at] = ps;
         }
       } else {
         col += fast_exp2(sv - lse_s[rg + 8 * x]);
@@ -195,7 +202,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
     if (PASS == 2 && tid < RCH) {
       const int r = r0 + tid;
       lse_reg = INFINITY;                     // padding rows contribute exp2(-inf) = 0
-      if (r < Rs) lse_reg = p.row_lse[((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G];
+      if (r < Rs) lse_reg = p.row_lse[((long long)b * p.Hkv + hk) * Rs + r];
     }
   };
   fetch_chunk(0);
@@ -269,10 +276,9 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 #pragma unroll
         for (int w = 0; w < NW; ++w)
           ll += (wm_s[w][rr] == -INFINITY) ? 0.f : wl_s[w][rr] * fast_exp2(wm_s[w][rr] - mm);
-        const int r = base + rr;
-        const long long row = ((long long)b * p.H + hk * p.G + r % p.G) * p.L + r / p.G;
-        p.row_m[row * p.n_tile + tile] = mm;
-        p.row_l[row * p.n_tile + tile] = ll;
+        const long long at = sattn_part_at(p, tile, b, hk, base + rr);   // consecutive rows: coalesced
+        p.row_m[at] = mm;
+        p.row_l[at] = ll;
       }
     }
   }
@@ -297,21 +303,47 @@ __global__ __launch_bounds__(kSaWaves * 64) void sattn_mfma(ScoreParams p) {
   sattn_mfma_body<D, PASS>(p, sm, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
-// merge the per-tile row statistics: lse2 = m* + log2(sum_t l_t 2^(m_t - m*)); one wave per row
+// merge the per-tile row statistics: lse2 = m* + log2(sum_t l_t 2^(m_t - m*)).  A block takes 32
+// consecutive rows; thread (row, slice s) merges tiles s, s+8, ... (loads issued 8 at a time), the 8
+// slices of a row then merge through LDS.  Consecutive threads read consecutive rows of a tile's slab.
 __global__ __launch_bounds__(256) void sattn_row_lse(ScoreParams p) {
-  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (row >= (long long)p.B * p.H * p.L) return;
-  float mm = -INFINITY;
-  for (int t = lane; t < p.n_tile; t += 64) mm = fmaxf(mm, p.row_m[row * p.n_tile + t]);
-  mm = wave_max(mm);
-  float ll = 0.f;
-  for (int t = lane; t < p.n_tile; t += 64) {
-    const float m = p.row_m[row * p.n_tile + t];
-    if (m != -INFINITY) ll += p.row_l[row * p.n_tile + t] * fast_exp2(m - mm);
+  __shared__ float sm[8][32], sl[8][32];
+  const long long rows = (long long)p.B * p.H * p.L;
+  const int rl = threadIdx.x & 31, slice = threadIdx.x >> 5;
+  const long long row = (long long)blockIdx.x * 32 + rl;
+  float mm = -INFINITY, ll = 0.f;
+  if (row < rows) {
+    for (int t0 = slice; t0 < p.n_tile; t0 += 64) {
+      float m[8], l[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int t = t0 + 8 * u;
+        m[u] = t < p.n_tile ? p.row_m[t * rows + row] : -INFINITY;
+        l[u] = t < p.n_tile ? p.row_l[t * rows + row] : 0.f;
+      }
+      float mx = mm;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) mx = fmaxf(mx, m[u]);
+      if (mx != -INFINITY) {
+        ll *= fast_exp2(mm - mx);                 // mm = -inf: ll is 0 and exp2(-inf) = 0
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ll += (m[u] != -INFINITY) ? l[u] * fast_exp2(m[u] - mx) : 0.f;
+        mm = mx;
+      }
+    }
   }
-  ll = wave_sum(ll);
-  if (lane == 0) p.row_lse[row] = mm + __log2f(ll);
+  sm[slice][rl] = mm;
+  sl[slice][rl] = ll;
+  __syncthreads();
+  if (slice == 0 && row < rows) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) mx = fmaxf(mx, sm[u][rl]);
+    float tot = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) tot += (sm[u][rl] != -INFINITY) ? sl[u][rl] * fast_exp2(sm[u][rl] - mx) : 0.f;
+    p.row_lse[row] = mx + __log2f(tot);
+  }
 }
 
 // s_attn[b,j] = sum_hk col_part / (H L)  (+ running layer sum)
@@ -849,7 +881,7 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
   dim3 grid(p.n_tile, p.Hkv, p.B);
   hipLaunchKernelGGL((sattn_valu<T, D, 1>), grid, dim3(256), 0, st, p);
   const long long rows = (long long)p.B * p.H * p.L;
-  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, p);
   hipLaunchKernelGGL((sattn_valu<T, D, 2>), grid, dim3(256), 0, st, p);
   return hipGetLastError();
 }
@@ -866,7 +898,7 @@ static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st, bool w
     hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(kSaWaves * 64), 0, st, p);
   }
   const long long rows = (long long)p.B * p.H * p.L;
-  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, p);
   hipLaunchKernelGGL((sattn_mfma<D, 2>), grid, dim3(kSaWaves * 64), 0, st, p);
   return hipGetLastError();
 }
