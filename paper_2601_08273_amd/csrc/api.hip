@@ -117,7 +117,7 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
 
 // ---- scoring planning ---------------------------------------------------------------------------
 struct ScorePlan {
-  int n_tile;
+  int n_tile, n_rsplit;
   size_t off_row_l, off_row_lse, off_col, off_sa, off_st, off_ss, bytes;
 };
 
@@ -130,7 +130,9 @@ int plan_score(const hippo_kv_desc* kv, const hippo_video_desc* vid, int l_txt, 
   const size_t rows = (size_t)kv->batch * kv->n_q_heads * l_txt;
   const size_t row_part = align_up(rows * pl->n_tile * sizeof(float), 256);
   const size_t row_lse = align_up(rows * sizeof(float), 256);
-  const size_t col = align_up((size_t)kv->batch * kv->n_kv_heads * Nv * sizeof(float), 256);
+  pl->n_rsplit = score_row_splits(kv->dtype, (long long)pl->n_tile * kv->n_kv_heads * kv->batch,
+                                  l_txt * (kv->n_q_heads / kv->n_kv_heads));
+  const size_t col = align_up((size_t)kv->batch * kv->n_kv_heads * pl->n_rsplit * Nv * sizeof(float), 256);
   const size_t vec = align_up((size_t)kv->batch * Nv * sizeof(float), 256);
   size_t o = 0;
   o += row_part;            pl->off_row_l = o;
@@ -255,6 +257,7 @@ int hippo_score_tokens(const void* q_txt, int32_t l_txt, const void* k_cache, co
   p.s_temp = reinterpret_cast<float*>(ws + pl.off_st);
   p.s_spa = reinterpret_cast<float*>(ws + pl.off_ss);
   p.n_tile = pl.n_tile;
+  p.n_rsplit = pl.n_rsplit;
   const hipError_t e = launch_score(p, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
 }

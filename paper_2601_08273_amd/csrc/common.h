@@ -106,14 +106,16 @@ struct ScoreParams {
   float* row_m;      // [n_tile, B, Hkv, L*G] partial row maxima (row r = i*G + g of a KV head)
   float* row_l;      // [n_tile, B, Hkv, L*G] partial row sums
   float* row_lse;    // [B, Hkv, L*G] final log2-domain row normaliser
-  float* col_part;   // [B, Hkv, Nv] per-KV-head column sums
+  float* col_part;   // [B, Hkv * n_rsplit, Nv] column sums per KV head and row run
   float* s_attn;     // [B, Nv]
   float* s_temp;     // [B, Nv]
   float* s_spa;      // [B, Nv]
   int n_tile;        // token tiles of pass 1
+  int n_rsplit;      // runs the query rows of a KV head are cut into (one block each)
 };
 hipError_t launch_score(const ScoreParams& p, hipStream_t st);
 int score_token_tile(int dtype);   // tokens per block in the s_attn passes
+int score_row_splits(int dtype, long long blocks_unsplit, int rows_per_kv_head);
 
 struct SelectParams {
   const float* scores;

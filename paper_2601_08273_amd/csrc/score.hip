@@ -127,7 +127,7 @@ template <int D, int PASS>
 struct SattnSmem {
   static constexpr int RCH = 64;                 // query rows per LDS chunk
   static constexpr int ROWB = D * 2 + 16;
-  static constexpr int RDEF = 512;               // pass 1 merges the waves' row statistics every RDEF rows
+  static constexpr int RDEF = 256;               // pass 1 merges the waves' row statistics every RDEF rows
   __align__(16) unsigned char Qs[RCH * ROWB];
   float lse_s[RCH];
   float wm_s[PASS == 1 ? kSaWaves : 1][PASS == 1 ? RDEF : 1];
@@ -136,7 +136,7 @@ struct SattnSmem {
 
 template <int D, int PASS>
 __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<D, PASS>& sm, const int tile,
-                                                const int hk, const int b) {
+                                                const int vhk, const int b) {
   constexpr int NW = kSaWaves, NT = NW * 64;
   constexpr int TPW = kSaMfmaTile / NW;   // tokens per wave
   constexpr int TBW = TPW / 16;           // 16-token blocks per wave
@@ -155,6 +155,11 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
   const int n0 = tile * kSaMfmaTile + wave * TPW;    // first token of this wave
   const int Rs = p.L * p.G;
   const float scale_log2 = rsqrtf((float)D) * kLog2e;
+  // the query rows of a KV head are cut into n_rsplit runs of whole chunks; this block sweeps one
+  const int hk = vhk / p.n_rsplit, rs = vhk % p.n_rsplit;
+  const int rows_per_split = ((Rs + RCH - 1) / RCH + p.n_rsplit - 1) / p.n_rsplit * RCH;
+  const int row_begin = rs * rows_per_split;
+  const int row_end = min(Rs, row_begin + rows_per_split);
 
   const uint16_t* kbase = (const uint16_t*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
                           (long long)p.vis_off * p.sn;
@@ -187,17 +192,30 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
   constexpr int QPT = (RCH * CPR + NT - 1) / NT;   // 16-byte pieces per thread per chunk
   u32x4 qreg[QPT];
   float lse_reg = INFINITY;
-  auto fetch_chunk = [&](int r0) {
+  // Row r = i*G + g of the KV head lives at ((b*L + i)*H + hk*G + g)*D.  The (i, g) of the rows this
+  // thread stages are carried from chunk to chunk (a chunk advances every row by RCH), so the
+  // division by G happens once, not per chunk.
+  const uint16_t* qbase = (const uint16_t*)p.q_txt + ((long long)b * p.L * p.H + hk * p.G) * D;
+  int qi[QPT], qg[QPT];
+  const int step_i = RCH / p.G, step_g = RCH % p.G;
+#pragma unroll
+  for (int u = 0; u < QPT; ++u) {
+    const int r = row_begin + (tid + NT * u) / CPR;
+    qi[u] = r / p.G;
+    qg[u] = r % p.G;
+  }
+  auto fetch_chunk = [&](int r0) {             // must be called with r0 = row_begin, +RCH, +2 RCH, ...
 #pragma unroll
     for (int u = 0; u < QPT; ++u) {
       const int e = tid + NT * u;
-      const int rr = e / CPR, ch = e % CPR, r = r0 + rr;
+      const int r = r0 + e / CPR;
       qreg[u] = (u32x4){0u, 0u, 0u, 0u};
-      if (e < RCH * CPR && r < Rs) {
-        const int i = r / p.G, gq = r % p.G;
-        qreg[u] = *(const u32x4*)((const uint16_t*)p.q_txt +
-                                  (((long long)b * p.L + i) * p.H + hk * p.G + gq) * D + ch * 8);
-      }
+      if (e < RCH * CPR && r < Rs)
+        qreg[u] = *(const u32x4*)(qbase + ((long long)qi[u] * p.H + qg[u]) * D + (e % CPR) * 8);
+      qg[u] += step_g;
+      const int carry = qg[u] >= p.G ? 1 : 0;
+      qg[u] -= carry * p.G;
+      qi[u] += step_i + carry;
     }
     if (PASS == 2 && tid < RCH) {
       const int r = r0 + tid;
@@ -205,8 +223,8 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
       if (r < Rs) lse_reg = p.row_lse[((long long)b * p.Hkv + hk) * Rs + r];
     }
   };
-  fetch_chunk(0);
-  for (int r0 = 0; r0 < Rs; r0 += RCH) {
+  fetch_chunk(row_begin);
+  for (int r0 = row_begin; r0 < row_end; r0 += RCH) {
     __syncthreads();                          // everyone is done with the previous chunk
 #pragma unroll
     for (int u = 0; u < QPT; ++u) {
@@ -215,11 +233,9 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
     }
     if (PASS == 2 && tid < RCH) lse_s[tid] = lse_reg;
     __syncthreads();
-    if (r0 + RCH < Rs) fetch_chunk(r0 + RCH);
+    if (r0 + RCH < row_end) fetch_chunk(r0 + RCH);
 
-#pragma unroll
-    for (int rb = 0; rb < RCH / 16; ++rb) {
-      f32x4 z[TBW];
+    auto products = [&](int rb, f32x4 (&z)[TBW]) {
 #pragma unroll
       for (int tb = 0; tb < TBW; ++tb) z[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -229,6 +245,8 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
         for (int tb = 0; tb < TBW; ++tb)
           z[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[tb][ks], qop, z[tb], 0, 0, 0);
       }
+    };
+    auto reduce = [&](int rb, f32x4 (&z)[TBW]) {
       if (PASS == 1) {
         if (!wave_full) {                       // wave-uniform: only the ragged last wave masks
 #pragma unroll
@@ -253,8 +271,8 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
         ps += __shfl_xor(ps, 16, 64);
         ps += __shfl_xor(ps, 32, 64);
         if (g == 0) {
-          wm_s[wave][(r0 % RDEF) + rb * 16 + j] = mx;
-          wl_s[wave][(r0 % RDEF) + rb * 16 + j] = ps;
+          wm_s[wave][((r0 - row_begin) % RDEF) + rb * 16 + j] = mx;
+          wl_s[wave][((r0 - row_begin) % RDEF) + rb * 16 + j] = ps;
         }
       } else {
         const float lse = lse_s[rb * 16 + j];
@@ -263,11 +281,17 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 #pragma unroll
           for (int e = 0; e < 4; ++e) col[tb][e] += fast_exp2(fmaf(z[tb][e], scale_log2, -lse));
       }
+    };
+#pragma unroll
+    for (int rb = 0; rb < RCH / 16; ++rb) {
+      f32x4 z[TBW];
+      products(rb, z);
+      reduce(rb, z);
     }
-    if (PASS == 1 && (((r0 + RCH) % RDEF) == 0 || r0 + RCH >= Rs)) {
+    if (PASS == 1 && (((r0 - row_begin + RCH) % RDEF) == 0 || r0 + RCH >= row_end)) {
       // merge the waves' (max, sum) of the rows gathered since the last merge and write them out
       __syncthreads();
-      const int base = r0 - (r0 % RDEF);
+      const int base = r0 - ((r0 - row_begin) % RDEF);
       for (int rr = tid; rr < RDEF && base + rr < Rs && base + rr < r0 + RCH; rr += NT) {
         float mm = -INFINITY;
 #pragma unroll
@@ -292,7 +316,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
         if (j == 0 && tok_ok[tb][e])
-          p.col_part[((long long)b * p.Hkv + hk) * p.Nv + n0 + tb * 16 + 4 * g + e] = v;
+          p.col_part[((long long)b * p.Hkv * p.n_rsplit + vhk) * p.Nv + n0 + tb * 16 + 4 * g + e] = v;
       }
   }
 }
@@ -352,7 +376,7 @@ __global__ __launch_bounds__(256) void sattn_finalize(ScoreParams p) {
   if (e >= (long long)p.B * p.Nv) return;
   const int b = (int)(e / p.Nv), jj = (int)(e % p.Nv);
   float a = 0.f;
-  for (int hk = 0; hk < p.Hkv; ++hk) a += p.col_part[((long long)b * p.Hkv + hk) * p.Nv + jj];
+  for (int hk = 0; hk < p.Hkv * p.n_rsplit; ++hk) a += p.col_part[((long long)b * p.Hkv * p.n_rsplit + hk) * p.Nv + jj];
   a /= (float)p.H * (float)p.L;
   if (p.attn_mass_inout != nullptr) {
     a += p.attn_mass_inout[e];
@@ -637,7 +661,8 @@ struct Emb32Smem {
   static constexpr int MP = 32;
   // blocks: Gram (0,0) (0,1) (1,1); then for prev and for next: dot rb0, dot rb1, norm rb0, norm rb1
   static constexpr int NBLK = 11;
-  f32x4 red[2][NBLK][64];                           // partial blocks of the two channel halves
+  f32x4 red[2][3][64];                              // Gram blocks of the two channel halves
+  float redd[2][NBLK - 3][16];                      // diagonals of the dot / norm blocks, likewise
   float G[MP][MP + 1];
   float tdot[4][MP];
   float inv_norm[MP];
@@ -652,6 +677,7 @@ __device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem&
   constexpr int MP = Emb32Smem::MP;
   constexpr int NBLK = Emb32Smem::NBLK;
   auto& red = sm.red;
+  auto& redd = sm.redd;
   auto& G = sm.G;
   auto& tdot = sm.tdot;
   auto& inv_norm = sm.inv_norm;
@@ -719,28 +745,35 @@ __device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem&
       }
     }
   }
+  // D[i][j']: a lane holds column j' = j, rows i = 4g..4g+3; of the dot / norm blocks only the
+  // diagonal (token with itself) is needed: lane (j, g = j/4), element j%4
   if (ig == 0) {
 #pragma unroll
-    for (int i = 0; i < 7; ++i) red[cg][i][lane] = acc[i];
-  } else {
+    for (int i = 0; i < 3; ++i) red[cg][i][lane] = acc[i];
+  }
+  if ((j >> 2) == g) {
+    const int e = j & 3;
 #pragma unroll
-    for (int i = 3; i < 7; ++i) red[cg][4 + i][lane] = acc[i];
+    for (int i = 3; i < 7; ++i) {
+      const float d = e == 0 ? acc[i][0] : e == 1 ? acc[i][1] : e == 2 ? acc[i][2] : acc[i][3];
+      redd[cg][(ig == 0 ? 0 : 4) + i - 3][j] = d;    // 0,1 prev dot; 2,3 prev norm; 4,5 next dot; 6,7 next norm
+    }
   }
   __syncthreads();
-  // sum the two channel halves; wave w finishes blocks w, w+4, ...
-  for (int blk = wave; blk < NBLK; blk += 4) {
+  // sum the two channel halves: waves 0..2 finish one Gram block each, wave 3 the diagonals
+  if (wave < 3) {
+    const int blk = wave;
     const f32x4 v = red[0][blk][lane] + red[1][blk][lane];
-    // D[i][j']: this lane holds column j' = j, rows i = 4g..4g+3
-    if (blk < 3) {
-      const int ra = blk == 2 ? 1 : 0, rbk = blk == 0 ? 0 : 1;
+    const int ra = blk == 2 ? 1 : 0, rbk = blk == 0 ? 0 : 1;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        G[ra * 16 + 4 * g + e][rbk * 16 + j] = v[e];
-        G[rbk * 16 + j][ra * 16 + 4 * g + e] = v[e];
-      }
-    } else if ((j >> 2) == g) {
-      const int t = blk - 3;               // 0,1 prev dot; 2,3 prev norm; 4,5 next dot; 6,7 next norm
-      tdot[t >> 1][(t & 1) * 16 + j] = v[j & 3];
+    for (int e = 0; e < 4; ++e) {
+      G[ra * 16 + 4 * g + e][rbk * 16 + j] = v[e];
+      G[rbk * 16 + j][ra * 16 + 4 * g + e] = v[e];
+    }
+  } else {
+    for (int e = lane; e < (NBLK - 3) * 16; e += 64) {
+      const int t = e >> 4, jj = e & 15;
+      tdot[t >> 1][(t & 1) * 16 + jj] = redd[0][t][jj] + redd[1][t][jj];
     }
   }
   __syncthreads();
@@ -782,12 +815,12 @@ __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
 }
 
 // Pass 1 of s_attn and the embedding terms in ONE launch: the first n_sattn blocks run the
-// (compute-bound, one block per compute unit) row-statistics sweep, the remaining blocks run two
-// crops each and fill the second block slot of every compute unit, so the memory-bound embedding
-// work hides under the sweep instead of following it.  Two blocks fit a compute unit: 8 waves of
-// at most 128 registers each and the larger of the two shared-memory layouts.
+// (compute-bound) row-statistics sweep, two per compute unit; the remaining blocks run two crops
+// each and fill the third block slot of every compute unit, so the memory-bound embedding work
+// hides under the sweep instead of following it.  Three blocks fit a compute unit: 8 waves of at
+// most 80 registers each and the larger of the two shared-memory layouts (34 KB).
 template <int D>
-__global__ __launch_bounds__(kSaWaves * 64, 4) void sattn_pass1_with_emb(ScoreParams p, int n_sattn) {
+__global__ __launch_bounds__(kSaWaves * 64, 6) void sattn_pass1_with_emb(ScoreParams p, int n_sattn) {
   union Smem {
     SattnSmem<D, 1> sa;
     Emb32Smem emb[2];
@@ -795,8 +828,8 @@ __global__ __launch_bounds__(kSaWaves * 64, 4) void sattn_pass1_with_emb(ScorePa
   __shared__ Smem sm;
   const int blk = blockIdx.x;
   if (blk < n_sattn) {
-    const int tile = blk % p.n_tile, rest = blk / p.n_tile;
-    sattn_mfma_body<D, 1>(p, sm.sa, tile, rest % p.Hkv, rest / p.Hkv);
+    const int tile = blk % p.n_tile, rest = blk / p.n_tile, nvh = p.Hkv * p.n_rsplit;
+    sattn_mfma_body<D, 1>(p, sm.sa, tile, rest % nvh, rest / nvh);
     return;
   }
   const int ncf = ((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw);   // crops per frame
@@ -830,7 +863,7 @@ __global__ __launch_bounds__(256) void fuse_scores(ScoreParams p) {
       const long long e = base + i;
       const int jj = f * p.P + i;
       float a = 0.f;
-      for (int hk = 0; hk < p.Hkv; ++hk) a += p.col_part[((long long)b * p.Hkv + hk) * p.Nv + jj];
+      for (int hk = 0; hk < p.Hkv * p.n_rsplit; ++hk) a += p.col_part[((long long)b * p.Hkv * p.n_rsplit + hk) * p.Nv + jj];
       a /= (float)p.H * (float)p.L;
       if (p.attn_mass_inout != nullptr) {
         a += p.attn_mass_inout[e];
@@ -876,6 +909,16 @@ __global__ __launch_bounds__(256) void fuse_scores(ScoreParams p) {
 // =================================================================================================
 int score_token_tile(int dtype) { return dtype == HIPPO_DTYPE_BF16 ? kSaMfmaTile : kSaValuTile; }
 
+// Row splits of the s_attn sweeps (bf16 path): enough blocks for two per compute unit, which is what
+// lets the MFMA and the exp work of different waves overlap; a split keeps at least two 64-row chunks.
+int score_row_splits(int dtype, long long blocks_unsplit, int rows_per_kv_head) {
+  if (dtype != HIPPO_DTYPE_BF16) return 1;
+  const int chunks = (rows_per_kv_head + 63) / 64;
+  int rs = 1;
+  while (rs < 4 && blocks_unsplit * rs < 2 * kNumCU && chunks / (rs * 2) >= 2) rs *= 2;
+  return rs;
+}
+
 template <typename T, int D>
 static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
   dim3 grid(p.n_tile, p.Hkv, p.B);
@@ -888,9 +931,9 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
 
 template <int D>
 static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st, bool with_emb) {
-  dim3 grid(p.n_tile, p.Hkv, p.B);
+  dim3 grid(p.n_tile, p.Hkv * p.n_rsplit, p.B);
   if (with_emb) {
-    const long long n_sattn = (long long)p.n_tile * p.Hkv * p.B;
+    const long long n_sattn = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.B;
     const long long n_crops = (long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B;
     hipLaunchKernelGGL((sattn_pass1_with_emb<D>), dim3((unsigned)(n_sattn + (n_crops + 1) / 2)),
                        dim3(kSaWaves * 64), 0, st, p, (int)n_sattn);
@@ -908,7 +951,7 @@ hipError_t launch_score(const ScoreParams& p, hipStream_t st) {
   const bool accumulate_only = (p.flags & HIPPO_SCORE_ACCUMULATE_ONLY) != 0;
   // bf16 with the paper's small crops: the embedding terms ride in the launch of s_attn's pass 1
   const bool want_emb = (p.flags & (HIPPO_SCORE_TEMP | HIPPO_SCORE_SPA)) != 0;
-  const long long fused_blocks = (long long)p.n_tile * p.Hkv * p.B +
+  const long long fused_blocks = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.B +
       ((long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B + 1) / 2;
   const bool emb_rides = want_emb && !accumulate_only && (p.flags & HIPPO_SCORE_ATTN) &&
                          p.dtype == HIPPO_DTYPE_BF16 && p.ch * p.cw <= 32 && fused_blocks < (1ll << 31);
