@@ -704,19 +704,31 @@ __device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem&
 
   // frames without a neighbour re-read the frame itself (finite data, result unused)
   const int dnb = ig == 0 ? (has_prev ? -1 : 0) : (has_next ? 1 : 0);
-  auto operand = [&](int df, int rbk, int ks) -> bf16x8 {
-    const int c = ks * 32 + g * 8;
-    if (ks >= n_ks || c >= de) return (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-    const long long tokn = tok_s[rbk * 16 + j] + (long long)df * p.P;
-    const uint16_t* src;
+  // Row pointers of this lane's two tokens (row blocks 0 and 1) in this frame and in the neighbour
+  // frame, computed once; a channel step then only adds its channel offset.  With keys as the
+  // embedding, channel c is element c % D of KV head c / D (D is a power of two).
+  const uint16_t* row_cur[2];
+  const uint16_t* row_nb[2];
+  const int dsh = p.D == 128 ? 7 : 6;
+#pragma unroll
+  for (int rbk = 0; rbk < 2; ++rbk) {
+    const long long tokn = tok_s[rbk * 16 + j];
     if (p.emb) {
-      src = (const uint16_t*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok + c;
+      row_cur[rbk] = (const uint16_t*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok;
+      row_nb[rbk] = row_cur[rbk] + (long long)dnb * p.P * p.emb_stride_tok;
     } else {
-      const int hk = c / p.D, cc = c % p.D;
-      src = (const uint16_t*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
-            (p.vis_off + tokn) * p.sn + cc;
+      row_cur[rbk] = (const uint16_t*)p.k_cache + (long long)b * p.sb + (p.vis_off + tokn) * p.sn;
+      row_nb[rbk] = row_cur[rbk] + (long long)dnb * p.P * p.sn;
     }
-    return *(const bf16x8*)src;
+  }
+  const bool keys_as_emb = p.emb == nullptr;
+  auto operand = [&](const uint16_t* row, int ks) -> bf16x8 {
+    const int c = ks * 32 + g * 8;
+    const bool ok = ks < n_ks && c < de;
+    const int cs = ok ? c : 0;                         // a valid address either way; zeroed below
+    const long long off = keys_as_emb ? (long long)(cs >> dsh) * p.sh + (cs & (p.D - 1)) : (long long)cs;
+    const bf16x8 v = *(const bf16x8*)(row + off);
+    return ok ? v : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
   };
 
   f32x4 acc[7];   // ig 0: Gram x3, dot x2, norm x2;  ig 1: (unused x3), dot x2, norm x2
@@ -728,8 +740,8 @@ __device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem&
     for (int u = 0; u < BATCH; ++u)
 #pragma unroll
       for (int rbk = 0; rbk < 2; ++rbk) {
-        cur[u][rbk] = operand(0, rbk, ks0 + 2 * u);
-        nb[u][rbk] = operand(dnb, rbk, ks0 + 2 * u);
+        cur[u][rbk] = operand(row_cur[rbk], ks0 + 2 * u);
+        nb[u][rbk] = operand(row_nb[rbk], ks0 + 2 * u);
       }
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
@@ -752,11 +764,12 @@ __device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem&
     for (int i = 0; i < 3; ++i) red[cg][i][lane] = acc[i];
   }
   if ((j >> 2) == g) {
-    const int e = j & 3;
 #pragma unroll
-    for (int i = 3; i < 7; ++i) {
-      const float d = e == 0 ? acc[i][0] : e == 1 ? acc[i][1] : e == 2 ? acc[i][2] : acc[i][3];
-      redd[cg][(ig == 0 ? 0 : 4) + i - 3][j] = d;    // 0,1 prev dot; 2,3 prev norm; 4,5 next dot; 6,7 next norm
+    for (int i = 3; i < 7; ++i) {                    // 0,1 prev dot; 2,3 prev norm; 4,5 next dot; 6,7 next norm
+      float* dst = &redd[cg][(ig == 0 ? 0 : 4) + i - 3][j];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if ((j & 3) == e) *dst = acc[i][e];
     }
   }
   __syncthreads();
