@@ -917,6 +917,84 @@ __global__ __launch_bounds__(256) void fuse_scores(ScoreParams p) {
   }
 }
 
+// The same for frames of at most 256 * NPT tokens: every value a thread needs is fetched in one
+// batch and stays in registers, and the three terms share each of the two block reductions, so a
+// frame costs one trip to memory instead of one per term and per moment.
+template <int NPT>
+__global__ __launch_bounds__(256) void fuse_scores_reg(ScoreParams p) {
+  __shared__ float red[3][4];
+  const int f = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long long base = (long long)b * p.Nv + (long long)f * p.P;
+  const int nvh = p.Hkv * p.n_rsplit;
+  const bool on[3] = {(p.flags & HIPPO_SCORE_ATTN) != 0, (p.flags & HIPPO_SCORE_TEMP) != 0,
+                      (p.flags & HIPPO_SCORE_SPA) != 0};
+  float x[3][NPT];
+#pragma unroll
+  for (int u = 0; u < NPT; ++u) {
+    const int i = tid + 256 * u;
+    const bool ok = i < p.P;
+    x[0][u] = x[1][u] = x[2][u] = 0.f;
+    if (ok && on[0]) {
+      float a = 0.f;
+      for (int hk = 0; hk < nvh; ++hk) a += p.col_part[((long long)b * nvh + hk) * p.Nv + (long long)f * p.P + i];
+      a /= (float)p.H * (float)p.L;
+      if (p.attn_mass_inout != nullptr) {
+        a += p.attn_mass_inout[base + i];
+        p.attn_mass_inout[base + i] = a;
+      }
+      p.s_attn[base + i] = a;
+      x[0][u] = a;
+    }
+    if (ok && on[1]) x[1][u] = p.s_temp[base + i];
+    if (ok && on[2]) x[2][u] = p.s_spa[base + i];
+  }
+  auto reduce3 = [&](float (&v)[3]) {                  // block sums of three values at once
+#pragma unroll
+    for (int t = 0; t < 3; ++t) v[t] = wave_sum(v[t]);
+    __syncthreads();
+    if (lane == 0) { red[0][wave] = v[0]; red[1][wave] = v[1]; red[2][wave] = v[2]; }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 3; ++t) v[t] = (red[t][0] + red[t][1]) + (red[t][2] + red[t][3]);
+  };
+  float mu[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+  for (int t = 0; t < 3; ++t)
+#pragma unroll
+    for (int u = 0; u < NPT; ++u) mu[t] += x[t][u];
+  reduce3(mu);
+  float var[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    mu[t] /= (float)p.P;
+#pragma unroll
+    for (int u = 0; u < NPT; ++u) {
+      const float d = (tid + 256 * u < p.P) ? x[t][u] - mu[t] : 0.f;
+      var[t] = fmaf(d, d, var[t]);
+    }
+  }
+  reduce3(var);
+  float inv_sigma[3];
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    var[t] /= (float)p.P;
+    inv_sigma[t] = (on[t] && var[t] > 0.f) ? 1.f / sqrtf(var[t]) : 0.f;
+  }
+#pragma unroll
+  for (int u = 0; u < NPT; ++u) {
+    const int i = tid + 256 * u;
+    if (i >= p.P) continue;
+    float sc = 0.f;
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      if (!on[t]) continue;
+      sc += (x[t][u] - mu[t]) * inv_sigma[t];
+      if (p.components_out) p.components_out[(long long)t * p.B * p.Nv + base + i] = x[t][u];
+    }
+    p.scores_out[base + i] = sc;
+  }
+}
+
 // =================================================================================================
 // host launch
 // =================================================================================================
@@ -993,7 +1071,9 @@ hipError_t launch_score(const ScoreParams& p, hipStream_t st) {
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(fuse_scores, dim3(p.F, p.B), dim3(256), 0, st, p);
+  if (p.P <= 256) hipLaunchKernelGGL(fuse_scores_reg<1>, dim3(p.F, p.B), dim3(256), 0, st, p);
+  else if (p.P <= 1024) hipLaunchKernelGGL(fuse_scores_reg<4>, dim3(p.F, p.B), dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(fuse_scores, dim3(p.F, p.B), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 

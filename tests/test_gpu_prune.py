@@ -46,6 +46,7 @@ def test_score_on_configs(hippo, name):
     (1, 33, 8, 2, 128, 5, 6, 11, 17, 5, (4, 3)),   # odd everything, 4x3 crops
     (1, 70, 7, 1, 128, 3, 13, 21, 8, 8, (5, 5)),   # 819 tokens: several tiles and a ragged tail
     (2, 5, 4, 4, 64, 4, 8, 8, 1, 0, (8, 8)),       # 64-token crops (the maximum)
+    (1, 4, 4, 2, 64, 2, 33, 32, 5, 3, (5, 5)),     # 1056-token frames: beyond the register-resident fusion
 ])
 def test_score_random_shapes(hippo, dtype, shape):
     B, L, H, Hkv, d, F, gh, gw, off, tail, (ch, cw) = shape
