@@ -108,20 +108,6 @@ __global__ __launch_bounds__(kSdThreads) void sd_row_stats(SpecParams p) {
   }
 }
 
-// merged statistics of one row from its segments
-__device__ __forceinline__ void merge_row(const SegStat* s, int n_seg, float c, float* m_out, float* z_out,
-                                          int* arg_out) {
-  float m = -INFINITY;
-  int arg = 0;
-  for (int i = 0; i < n_seg; ++i)
-    if (s[i].m > m) { m = s[i].m; arg = s[i].arg; }       // segments ascend: strict > keeps the first
-  float z = 0.f;
-  if (c > 0.f)
-    for (int i = 0; i < n_seg; ++i)
-      if (s[i].m > -INFINITY) z += s[i].z * fast_exp2((s[i].m - m) * c);
-  *m_out = m; *z_out = z; *arg_out = arg;
-}
-
 // Eq. 1 for all positions, first rejection, and (sampling mode) the cell sums of the distribution
 // the next token is drawn from.  Blocks of one sequence repeat the small first part identically.
 template <typename T>
@@ -158,38 +144,61 @@ __global__ __launch_bounds__(kSdThreads) void sd_cells(SpecParams p) {
     for (int i = tid; i < n_stats; i += kSdThreads) sh_stats[i] = st[i];
     __syncthreads();
   }
-  if (tid <= p.gamma) {
-    float m, z; int a;
-    if (staged) merge_row(sh_stats + tid * p.n_seg, p.n_seg, p.c, &m, &z, &a);
-    else merge_row(st + (long long)tid * p.n_seg, p.n_seg, p.c, &m, &z, &a);
-    sh_mp[tid] = m; sh_zp[tid] = z; sh_argp[tid] = a;
-    if (tid < p.gamma) {
-      double alpha;
-      float mq = 0.f, zq = 1.f;
-      if (!greedy) {
-        int aq;
-        if (staged) merge_row(sh_stats + (p.gamma + 1 + tid) * p.n_seg, p.n_seg, p.c, &mq, &zq, &aq);
-        else merge_row(st + (long long)(p.gamma + 1 + tid) * p.n_seg, p.n_seg, p.c, &mq, &zq, &aq);
-        sh_mq[tid] = mq; sh_zq[tid] = zq;
+  // merged statistics of every row: one row per group of 16 lanes (lanes over segments), so the
+  // merges run side by side instead of one thread walking each row
+  {
+    const int n_r = greedy ? p.gamma + 1 : p.n_rows;
+    const int grp = tid >> 4, gl = tid & 15;
+    for (int row = grp; row < n_r; row += kSdThreads / 16) {
+      const SegStat* rs = staged ? sh_stats + row * p.n_seg : st + (long long)row * p.n_seg;
+      float m = -INFINITY;
+      int arg = 0x7fffffff;
+      for (int i = gl; i < p.n_seg; i += 16) {
+        const float sm_ = rs[i].m;
+        const int sa_ = rs[i].arg;
+        if (sm_ > m || (sm_ == m && sa_ < arg)) { m = sm_; arg = sa_; }
       }
-      if (x < 0 || x >= p.V) {
-        alpha = 0.0;                                        // not a word: rejected
-      } else if (greedy) {
-        alpha = (x == a) ? 1.0 : 0.0;
-      } else {
-        const double lp = (double)lp_raw - (double)m;
-        const double lq = (double)lq_raw - (double)mq;
-        // p[x] / q[x] = exp((lp - lq) / T) * zq / zp;  p[x] = 0 -> 0;  q[x] = 0 -> p >= q -> 1
-        if (lp == -INFINITY) alpha = (lq == -INFINITY) ? 1.0 : 0.0;
-        else if (lq == -INFINITY) alpha = 1.0;
-        else {
-          const double ratio = exp((lp - lq) * p.inv_temperature) * ((double)zq / (double)z);
-          alpha = ratio >= 1.0 ? 1.0 : ratio;
-        }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) {
+        const float om = __shfl_xor(m, o, 64);
+        const int oa = __shfl_xor(arg, o, 64);
+        if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
       }
-      sh_rej[tid] = greedy ? (alpha == 0.0) : !((double)u < alpha);
-      if (seg == 0 && p.alpha_out) p.alpha_out[(long long)b * p.gamma + tid] = (float)alpha;
+      float z = 0.f;
+      if (!greedy)
+        for (int i = gl; i < p.n_seg; i += 16)
+          if (rs[i].m > -INFINITY) z += rs[i].z * fast_exp2((rs[i].m - m) * p.c);
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
+      if (gl == 0) {
+        if (row <= p.gamma) { sh_mp[row] = m; sh_zp[row] = z; sh_argp[row] = arg; }
+        else { sh_mq[row - p.gamma - 1] = m; sh_zq[row - p.gamma - 1] = z; }
+      }
     }
+  }
+  __syncthreads();
+  if (tid < p.gamma) {
+    const float m = sh_mp[tid], z = sh_zp[tid];
+    const int a = sh_argp[tid];
+    double alpha;
+    if (x < 0 || x >= p.V) {
+      alpha = 0.0;                                        // not a word: rejected
+    } else if (greedy) {
+      alpha = (x == a) ? 1.0 : 0.0;
+    } else {
+      const float mq = sh_mq[tid], zq = sh_zq[tid];
+      const double lp = (double)lp_raw - (double)m;
+      const double lq = (double)lq_raw - (double)mq;
+      // p[x] / q[x] = exp((lp - lq) / T) * zq / zp;  p[x] = 0 -> 0;  q[x] = 0 -> p >= q -> 1
+      if (lp == -INFINITY) alpha = (lq == -INFINITY) ? 1.0 : 0.0;
+      else if (lq == -INFINITY) alpha = 1.0;
+      else {
+        const double ratio = exp((lp - lq) * p.inv_temperature) * ((double)zq / (double)z);
+        alpha = ratio >= 1.0 ? 1.0 : ratio;
+      }
+    }
+    sh_rej[tid] = greedy ? (alpha == 0.0) : !((double)u < alpha);
+    if (seg == 0 && p.alpha_out) p.alpha_out[(long long)b * p.gamma + tid] = (float)alpha;
   }
   __syncthreads();
   if (tid == 0) {
@@ -202,7 +211,10 @@ __global__ __launch_bounds__(kSdThreads) void sd_cells(SpecParams p) {
   const int j = sh_j;
   const bool rejected = j < p.gamma;
   if (greedy) {
-    if (tid == 0) { p.n_accept[b] = j; p.next_token[b] = sh_argp[j]; }
+    if (tid == 0) {
+      p.n_accept[b] = j;
+      p.next_token[b] = (sh_argp[j] >= 0 && sh_argp[j] < p.V) ? sh_argp[j] : 0;   // a row without a finite logit
+    }
     return;
   }
   const float mp = sh_mp[j], inv_zp = 1.0f / sh_zp[j];
