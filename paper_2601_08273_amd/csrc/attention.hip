@@ -530,14 +530,22 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
                        : (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  float mloc = -INFINITY;
-  for (int s = tid; s < p.S; s += 256) mloc = fmaxf(mloc, p.part_m[(slot0 + s) * p.R + r]);
+  // this thread's first slice statistics ride in the same trip (S <= 256 is the usual case)
+  const float m0 = tid < p.S ? p.part_m[(slot0 + tid) * p.R + r] : -INFINITY;
+  const float l0 = tid < p.S ? p.part_l[(slot0 + tid) * p.R + r] : 0.f;
+  float mloc = m0;
+  for (int s = tid + 256; s < p.S; s += 256) mloc = fmaxf(mloc, p.part_m[(slot0 + s) * p.R + r]);
   mloc = wave_max(mloc);
   if ((tid & 63) == 0) red[tid >> 6] = mloc;
   __syncthreads();
   const float mstar = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   float dloc = 0.f;
-  for (int s = tid; s < p.S; s += 256) {
+  if (tid < p.S) {
+    const float w = (m0 == -INFINITY) ? 0.f : fast_exp2(m0 - mstar);
+    w_s[tid] = w;
+    dloc = w * l0;
+  }
+  for (int s = tid + 256; s < p.S; s += 256) {
     const float ms = p.part_m[(slot0 + s) * p.R + r];
     const float w = (ms == -INFINITY) ? 0.f : fast_exp2(ms - mstar);
     w_s[s] = w;
