@@ -42,6 +42,7 @@ struct AttnPlan {
 };
 
 int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, int num_splits, AttnPlan* pl) {
+  (void)call;   // draft and verify share one heuristic today
   if (q_len < 1 || n_total < q_len || num_splits < 0) return HIPPO_ERR_BAD_SHAPE;
   const int G = kv->n_q_heads / kv->n_kv_heads;
   if ((long long)G * q_len > 4096) return HIPPO_ERR_BAD_SHAPE;
@@ -62,11 +63,10 @@ int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, in
   const int n_tiles = (n_total + tile - 1) / tile;
   int S = num_splits;
   if (S == 0) {
-    // one block per compute unit (two for the short draft cache, whose blocks are tiny), but
-    // never slices thinner than a tile per wave
+    // one block per compute unit (measured at the 16K configuration: 48 or 80-128 slices per KV head
+    // are all slower than 64), but never slices thinner than a tile per wave
     const long long per_split = (long long)kv->batch * kv->n_kv_heads * pl->n_chunks;
-    const long long target = (call == HIPPO_CALL_DRAFT_ATTENTION) ? kNumCU : kNumCU;
-    S = (int)((target + per_split - 1) / per_split);
+    S = (int)((kNumCU + per_split - 1) / per_split);
     const int cap = n_tiles / min_tiles_per_block;
     if (S > cap) S = cap;
   }
