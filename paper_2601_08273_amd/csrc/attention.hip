@@ -401,8 +401,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     }
     float m8 = fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3]));
     if (TB == 2) m8 = fmaxf(m8, fmaxf(fmaxf(s[TB - 1][0], s[TB - 1][1]), fmaxf(s[TB - 1][2], s[TB - 1][3])));
-    m8 = fmaxf(m8, __shfl_xor(m8, 16, 64));
-    m8 = fmaxf(m8, __shfl_xor(m8, 32, 64));
+    m8 = rows4_max(m8);
     const float mx = m8 * p.scale_log2;                    // scale > 0: max commutes with it
     // lazy rescale: the reference m_run moves only when the tile maximum exceeds it by more than
     // kRescaleGap, so probabilities stay below 2^kRescaleGap and rescales are rare
@@ -459,8 +458,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   HIPPO_TP(6)
 
   // ---- merge the TG token groups of every row block ----
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
+  l_run = rows4_sum(l_run);
   if (g == 0) {
     stat_m[tg * RB * 16 + rb * 16 + j] = m_run;
     stat_l[tg * RB * 16 + rb * 16 + j] = l_run;

@@ -61,6 +61,24 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// Reductions over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48), result in every
+// lane.  v_permlane16_swap / v_permlane32_swap exchange whole rows inside the vector ALU: called
+// with the same value twice they return (even rows' value, odd rows' value) resp. (lower half's,
+// upper half's) in every lane, so one swap and one max / add replace a trip through the LDS
+// crossbar (ds_bpermute) per step.
+__device__ __forceinline__ float rows4_max(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows4_sum(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- host side ---------------------------------------------------------------------------------

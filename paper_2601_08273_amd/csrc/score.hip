@@ -259,8 +259,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 #pragma unroll
         for (int tb = 0; tb < TBW; ++tb)
           mx = fmaxf(mx, fmaxf(fmaxf(z[tb][0], z[tb][1]), fmaxf(z[tb][2], z[tb][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = rows4_max(mx);
         mx *= scale_log2;
         const float neg_m = (mx == -INFINITY) ? 0.f : -mx;
         float ps = 0.f;
@@ -268,8 +267,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
         for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
           for (int e = 0; e < 4; ++e) ps += fast_exp2(fmaf(z[tb][e], scale_log2, neg_m));
-        ps += __shfl_xor(ps, 16, 64);
-        ps += __shfl_xor(ps, 32, 64);
+        ps = rows4_sum(ps);
         if (g == 0) {
           wm_s[wave][((r0 - row_begin) % RDEF) + rb * 16 + j] = mx;
           wl_s[wave][((r0 - row_begin) % RDEF) + rb * 16 + j] = ps;
