@@ -182,7 +182,10 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 // Issued from inline assembly with hand-placed vmcnt waits: the compiler would otherwise wait for
 // every outstanding transfer before each LDS read.
 __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
+  // the address is wave-uniform by construction; readfirstlane tells the compiler so where its own
+  // analysis cannot (it must end up in a scalar register to reach M0)
+  const unsigned uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform_addr)
                : "memory");
 }
 template <int N>
@@ -317,7 +320,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 
   HIPPO_TP_DECL
   HIPPO_TP(0)
-  // ---- prologue: the query block, then every ring stage ----
+  // ---- prologue: the first ring stage goes out before anything else (its bytes are the ones
+  // the first products wait for), then the query block, then the remaining stages.  Transfers
+  // complete in issue order, so the wait for super-tile 0 below also covers the query block. ----
+  const bool issuer = wave < ISSUERS;
+  int issued = n_super < NST ? n_super : NST;              // super-tiles requested so far
+  if (issuer && issued > 0) issue_super(0);
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     if ((n % WAVES) == wave) {
@@ -330,10 +338,8 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       dma16(src, q_addr + n * 1024);
     }
   }
-  const bool issuer = wave < ISSUERS;
-  int issued = n_super < NST ? n_super : NST;              // super-tiles requested so far
   if (issuer)
-    for (int si = 0; si < issued; ++si) issue_super(si);
+    for (int si = 1; si < issued; ++si) issue_super(si);
 
   const int row = r0 + rb * 16 + j;                       // this lane's query row
   const int lim = (row < p.R) ? p.ctx_len + row / p.G : 0x7fffffff;
