@@ -358,6 +358,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 #pragma unroll
   for (int db = 0; db < DB; ++db)
     v_off[db] = v_row * ROWB + (((2 * db + ((j & 3) >> 1)) ^ swz_v) * 16) + (j & 1) * 8;
+  // keep the swizzled lane offsets in registers: left to itself the compiler recomputes them from
+  // (j, g) for every tile, which costs more vector instructions than the tile's arithmetic
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(k_off[ks]));
+#pragma unroll
+  for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(v_off[db]));
 
   bf16x8 qop[KS];
   int trace_it = 0;
