@@ -145,6 +145,23 @@ def main():
             h.hippo_draft_attention(qdraft[l], kp[l], vp[l], n_dctx, out=out_dr, workspace=ws_dr, stream=sB)
         cur.wait_stream(sB)
 
+    # appended-row fusion: the q_len new rows arrive as [B, q_len, Hkv, d] and reach the cache inside
+    # the attention launch, versus a separate copy (two strided copies, K and V) followed by the call
+    k_new = [kd[l][:, :, n_ctx:n_tot].transpose(1, 2).contiguous() for l in range(L)]
+    v_new = [vd[l][:, :, n_ctx:n_tot].transpose(1, 2).contiguous() for l in range(L)]
+
+    def verify_append_all():
+        for l in range(L):
+            h.hippo_verify_attention(qd[l], kd[l], vd[l], n_ctx, num_splits=args.num_splits, out=out_ver,
+                                     workspace=ws_ver, k_new=k_new[l], v_new=v_new[l])
+
+    def copy_then_verify_all():
+        for l in range(L):
+            kd[l][:, :, n_ctx:n_tot].copy_(k_new[l].transpose(1, 2))
+            vd[l][:, :, n_ctx:n_tot].copy_(v_new[l].transpose(1, 2))
+            h.hippo_verify_attention(qd[l], kd[l], vd[l], n_ctx, num_splits=args.num_splits, out=out_ver,
+                                     workspace=ws_ver)
+
     def score_only():
         h.hippo_score_tokens(q_txt, kd[0][:, :, :n_ctx], vid, scores_out=scores, workspace=ws_score)
 
@@ -188,6 +205,8 @@ def main():
     run_verify = capture(verify_all)
     run_draft = capture(draft_all)
     run_score = capture(score_only)
+    run_verify_append = capture(verify_append_all)
+    run_copy_verify = capture(copy_then_verify_all)
     run_sd_sampling = capture(spec_sampling)
     run_sd_greedy = capture(spec_greedy)
     torch.cuda.synchronize()
@@ -237,6 +256,8 @@ def main():
     t_draft_alone = alone(run_draft) / L
     t_score_alone = alone(run_score)
     t_prune_alone = alone(run_prune)
+    t_verify_append = alone(run_verify_append) / L
+    t_copy_verify = alone(run_copy_verify) / L
     t_sd_sampling = alone(run_sd_sampling) / SD_REPS
     t_sd_greedy = alone(run_sd_greedy) / SD_REPS
 
@@ -281,6 +302,8 @@ def main():
                "alone:draft_per_layer": round(t_draft_alone * 1e6, 3),
                "alone:score_tokens": round(t_score_alone * 1e6, 2),
                "alone:prune": round(t_prune_alone * 1e6, 2),
+               "alone:verify_with_fused_append_per_layer": round(t_verify_append * 1e6, 3),
+               "alone:copy_new_rows_then_verify_per_layer": round(t_copy_verify * 1e6, 3),
                "alone:spec_verify(sampling, V=%d)" % V: round(t_sd_sampling * 1e6, 2),
                "alone:spec_verify(greedy, V=%d)" % V: round(t_sd_greedy * 1e6, 2)},
         "verify_alone_GBps": round(kv_bytes / t_verify_alone / 1e9, 1),

@@ -179,6 +179,28 @@ int hippo_draft_attention(const void* q, int32_t q_len,
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same two attention calls with the append of the new rows folded in (a cache-format variant for
+ * decode loops: the gamma+1 rows the target verifies, or the one row the draft model decodes, come
+ * straight from the K/V projection and would otherwise need a copy kernel of their own before the
+ * attention launch).  k_new, v_new [B, q_len, H_kv, d] contiguous, dtype kv->dtype: the new rows'
+ * keys and values.  The result is exactly that of hippo_verify_attention / hippo_draft_attention on
+ * a cache whose rows ctx_len .. ctx_len + q_len - 1 hold them; the call also WRITES those rows into
+ * k_cache / v_cache (bit copies), so the next call finds them there.  Rows below ctx_len are read
+ * only.  k_new / v_new must not overlap the caches.  Everything else as above.
+ * Errors: as above, plus NULL_ARG / BAD_ALIGN for k_new, v_new.
+ */
+int hippo_verify_attention_append(const void* q, int32_t q_len, const void* k_new, const void* v_new,
+                                  void* k_cache, void* v_cache, const hippo_kv_desc* kv,
+                                  int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                                  void* out, float* lse_out,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+int hippo_draft_attention_append(const void* q, int32_t q_len, const void* k_new, const void* v_new,
+                                 void* k_cache, void* v_cache, const hippo_kv_desc* kv,
+                                 int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                                 void* out, float* lse_out,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Speculative-sampling verification of one chain of gamma draft tokens per sequence
  * (Preliminaries, "Speculative Decoding": Eq. 1, the resampling rule below it, and the extra token
  * after a full acceptance; Method, "Adaptive Decoding Strategy Switching": conservative mode

@@ -20,6 +20,7 @@ OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO
 
 EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
            "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention",
+           "hippo_verify_attention_append", "hippo_draft_attention_append",
            "hippo_spec_verify_workspace_bytes", "hippo_spec_verify", "hippo_vpsd_prefill_buffer",
            "hippo_vpsd_init", "hippo_vpsd_plan", "hippo_vpsd_commit", "hippo_vpsd_simulate")
 VPSD_CONSERVATIVE, VPSD_OPTIMISTIC = 0, 1
@@ -84,6 +85,9 @@ def load():
     lib.hippo_select_gather_kv.restype = C.c_int
     for fn in (lib.hippo_verify_attention, lib.hippo_draft_attention):
         fn.argtypes = [vp, i32, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
+        fn.restype = C.c_int
+    for fn in (lib.hippo_verify_attention_append, lib.hippo_draft_attention_append):
+        fn.argtypes = [vp, i32, vp, vp, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
     f64 = C.c_double
     lib.hippo_vpsd_prefill_buffer.argtypes = [f64, f64, f64]
@@ -226,7 +230,7 @@ def hippo_select_gather_kv(scores, k: int, k_src, v_src, vid: VideoDesc, n_q_hea
 
 
 def _attention(fn_name, call, q, k_cache, v_cache, ctx_len, softmax_scale, num_splits, want_lse, out,
-               workspace, stream):
+               workspace, stream, k_new=None, v_new=None):
     torch = _torch()
     lib = load()
     assert q.is_contiguous() and q.dim() == 4
@@ -238,6 +242,16 @@ def _attention(fn_name, call, q, k_cache, v_cache, ctx_len, softmax_scale, num_s
     if out is None:
         out = torch.empty_like(q)
     lse = torch.empty((B, H, q_len), dtype=torch.float32, device=q.device) if want_lse else None
+    if k_new is not None:
+        fn_name += "_append"
+        Hkv = k_cache.shape[1]
+        for t in (k_new, v_new):
+            assert t.shape == (B, q_len, Hkv, d) and t.is_contiguous() and t.dtype == k_cache.dtype
+        st = getattr(lib, fn_name)(_ptr(q), q_len, _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                   C.byref(kv), ctx_len, float(softmax_scale or 0.0), num_splits, _ptr(out),
+                                   _ptr(lse), _ptr(ws), ws.numel(), _stream(stream))
+        _check(st, fn_name)
+        return (out, lse) if want_lse else out
     st = getattr(lib, fn_name)(_ptr(q), q_len, _ptr(k_cache), _ptr(v_cache), C.byref(kv), ctx_len,
                                float(softmax_scale or 0.0), num_splits, _ptr(out), _ptr(lse), _ptr(ws),
                                ws.numel(), _stream(stream))
@@ -246,16 +260,18 @@ def _attention(fn_name, call, q, k_cache, v_cache, ctx_len, softmax_scale, num_s
 
 
 def hippo_verify_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: float = 0.0, num_splits: int = 0,
-                           want_lse: bool = False, out=None, workspace=None, stream=None):
-    """q [B,q_len,H,d]; caches hold ctx_len+q_len rows; row i attends to [0, ctx_len+i]."""
+                           want_lse: bool = False, out=None, workspace=None, stream=None, k_new=None, v_new=None):
+    """q [B,q_len,H,d]; caches hold ctx_len+q_len rows; row i attends to [0, ctx_len+i].
+    With k_new / v_new [B,q_len,Hkv,d] the new rows are taken from there and appended to the caches
+    by the same launch (hippo_verify_attention_append)."""
     return _attention("hippo_verify_attention", CALL_VERIFY_ATTENTION, q, k_cache, v_cache, ctx_len,
-                      softmax_scale, num_splits, want_lse, out, workspace, stream)
+                      softmax_scale, num_splits, want_lse, out, workspace, stream, k_new, v_new)
 
 
 def hippo_draft_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: float = 0.0, num_splits: int = 0,
-                          want_lse: bool = False, out=None, workspace=None, stream=None):
+                          want_lse: bool = False, out=None, workspace=None, stream=None, k_new=None, v_new=None):
     return _attention("hippo_draft_attention", CALL_DRAFT_ATTENTION, q, k_cache, v_cache, ctx_len,
-                      softmax_scale, num_splits, want_lse, out, workspace, stream)
+                      softmax_scale, num_splits, want_lse, out, workspace, stream, k_new, v_new)
 
 
 def hippo_spec_verify(p_logits, q_logits, draft_tokens, u_accept, u_sample, temperature: float,

@@ -85,15 +85,18 @@ int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, in
 
 int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache, const void* v_cache,
                     const hippo_kv_desc* kv, int32_t ctx_len, float softmax_scale, int32_t num_splits,
-                    void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+                    void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream,
+                    bool append = false, const void* k_new = nullptr, const void* v_new = nullptr) {
   if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr || workspace == nullptr)
     return HIPPO_ERR_NULL_ARG;
+  if (append && (k_new == nullptr || v_new == nullptr)) return HIPPO_ERR_NULL_ARG;
   int rc = check_kv(kv);
   if (rc != HIPPO_OK) return rc;
   if (ctx_len < 0 || q_len < 1 || (long long)ctx_len + q_len > 0x7fffff00ll) return HIPPO_ERR_BAD_SHAPE;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return HIPPO_ERR_BAD_ALIGN;
+  if (append && (!aligned16(k_new) || !aligned16(v_new))) return HIPPO_ERR_BAD_ALIGN;
   AttnPlan pl;
   rc = plan_attention(call, kv, q_len, ctx_len + q_len, num_splits, &pl);
   if (rc != HIPPO_OK) return rc;
@@ -111,6 +114,8 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)kv->head_dim);
   p.scale_log2 = scale * kLog2e;
   p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks; p.variant = 0;
+  p.k_new = append ? k_new : nullptr; p.v_new = append ? v_new : nullptr;
+  p.k_w = const_cast<void*>(k_cache); p.v_w = const_cast<void*>(v_cache);
   const hipError_t e = launch_attention(p, kv->dtype, kv->head_dim, pl.mfma, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
 }
@@ -356,6 +361,22 @@ int hippo_spec_verify(const void* p_logits, const void* q_logits, int32_t dtype,
   p.chosen = reinterpret_cast<Chosen*>(ws + pl.off_chosen);
   const hipError_t e = launch_spec_verify(p, dtype, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
+}
+
+int hippo_verify_attention_append(const void* q, int32_t q_len, const void* k_new, const void* v_new,
+                                  void* k_cache, void* v_cache, const hippo_kv_desc* kv, int32_t ctx_len,
+                                  float softmax_scale, int32_t num_splits, void* out, float* lse_out,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_entry(HIPPO_CALL_VERIFY_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream, true, k_new, v_new);
+}
+
+int hippo_draft_attention_append(const void* q, int32_t q_len, const void* k_new, const void* v_new,
+                                 void* k_cache, void* v_cache, const hippo_kv_desc* kv, int32_t ctx_len,
+                                 float softmax_scale, int32_t num_splits, void* out, float* lse_out,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream, true, k_new, v_new);
 }
 
 }  // extern "C"

@@ -35,6 +35,22 @@ namespace hippo {
 // =================================================================================================
 // Vector-ALU partial kernel
 // =================================================================================================
+// Appended-row fusion: the q_len new K/V rows of (b, hk) go from k_new / v_new [B, q_len, Hkv, D] into
+// cache rows ctx_len.., bit for bit.  Called by one block per (b, hk) after its own transfers have
+// drained; no block of this launch reads those cache rows (they all read k_new / v_new instead).
+template <typename T, int D>
+__device__ __forceinline__ void append_new_rows(const AttnParams& p, int b, int hk) {
+  constexpr int VPR = D / Elem<T>::kPerVec;    // 16-byte pieces per row
+  for (int e = threadIdx.x; e < p.q_len * VPR; e += blockDim.x) {
+    const int nr = e / VPR, pc = e % VPR;
+    const long long src = (((long long)b * p.q_len + nr) * p.Hkv + hk) * D + pc * Elem<T>::kPerVec;
+    const long long dst = (long long)b * p.sb + (long long)hk * p.sh + (long long)(p.ctx_len + nr) * p.sn +
+                          pc * Elem<T>::kPerVec;
+    *(u32x4*)((T*)p.k_w + dst) = *(const u32x4*)((const T*)p.k_new + src);
+    *(u32x4*)((T*)p.v_w + dst) = *(const u32x4*)((const T*)p.v_new + src);
+  }
+}
+
 constexpr int kValuTile = 32;   // tokens per tile
 constexpr int kValuRows = 32;   // query rows per block
 
@@ -98,8 +114,15 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
       const int row = e / VPR, vec = e % VPR, n = n0 + row;
       float kf[Elem<T>::kPerVec], vf[Elem<T>::kPerVec];
       if (n < p.n_total) {
-        const u32x4 kv4 = *(const u32x4*)(kbase + (long long)n * p.sn + vec * Elem<T>::kPerVec);
-        const u32x4 vv4 = *(const u32x4*)(vbase + (long long)n * p.sn + vec * Elem<T>::kPerVec);
+        const T* ks = kbase + (long long)n * p.sn;
+        const T* vs = vbase + (long long)n * p.sn;
+        if (p.k_new != nullptr && n >= p.ctx_len) {          // a row that has not reached the cache yet
+          const long long o = (((long long)b * p.q_len + (n - p.ctx_len)) * p.Hkv + hk) * D;
+          ks = (const T*)p.k_new + o;
+          vs = (const T*)p.v_new + o;
+        }
+        const u32x4 kv4 = *(const u32x4*)(ks + vec * Elem<T>::kPerVec);
+        const u32x4 vv4 = *(const u32x4*)(vs + vec * Elem<T>::kPerVec);
         Elem<T>::unpack(kv4, kf);
         Elem<T>::unpack(vv4, vf);
       } else {
@@ -167,6 +190,7 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
       }
     }
   }
+  if (p.k_new != nullptr && split == 0 && chunk == 0) append_new_rows<T, D>(p, b, hk);
 }
 
 // =================================================================================================
@@ -250,7 +274,7 @@ struct GridSmem {
 };
 
 // TT = tokens per tile (16 or 32), NST = ring stages (super-tiles resident in LDS)
-template <int D, int RB, int TG, int TT, int NST>
+template <int D, int RB, int TG, int TT, int NST, bool APPEND>
 __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) {
   using SM = GridSmem<D, TG, TT, NST>;
   constexpr int WAVES = RB * TG;
@@ -313,8 +337,11 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       const int r = n * RPI + ld_row;
       long long row = (long long)(tile0 + tt) * TT + r;
       row = row < row_cap ? row : row_cap;
-      dma16((which ? vbase : kbase) + row * row_bytes + ((ld_pc ^ ((r / RPS) & (CPR - 1))) * 16),
-            dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
+      const char* src = (which ? vbase : kbase) + row * row_bytes;
+      if (APPEND && row >= p.ctx_len)                      // a row that has not reached the cache yet
+        src = (const char*)(which ? p.v_new : p.k_new) +
+              ((((long long)b * p.q_len + (row - p.ctx_len)) * p.Hkv + hk) * D) * 2;
+      dma16(src + ((ld_pc ^ ((r / RPS) & (CPR - 1))) * 16), dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
     }
   };
 
@@ -507,6 +534,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   }
   HIPPO_TP(8)
   HIPPO_TP_FLUSH
+  if (APPEND && split == 0 && chunk == 0) append_new_rows<uint16_t, D>(p, b, hk);
 }
 
 // =================================================================================================
@@ -596,19 +624,26 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
 // =================================================================================================
 // host launch
 // =================================================================================================
-template <int D, int RB, int TG, int TT, int NST>
-static hipError_t launch_grid(const AttnParams& p, hipStream_t st) {
+template <int D, int RB, int TG, int TT, int NST, bool APPEND>
+static hipError_t launch_grid_ap(const AttnParams& p, hipStream_t st) {
   constexpr int smem = GridSmem<D, TG, TT, NST>::total(RB);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST>,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, APPEND>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid(p.S, p.Hkv, p.B * p.n_chunks);
-  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST>), grid, dim3(RB * TG * 64), smem, st, p);
+  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, APPEND>), grid, dim3(RB * TG * 64), smem, st, p);
   return hipGetLastError();
+}
+
+// the appended-row variant is a separate instantiation, so the plain call carries none of its selects
+template <int D, int RB, int TG, int TT, int NST>
+static hipError_t launch_grid(const AttnParams& p, hipStream_t st) {
+  return p.k_new != nullptr ? launch_grid_ap<D, RB, TG, TT, NST, true>(p, st)
+                            : launch_grid_ap<D, RB, TG, TT, NST, false>(p, st);
 }
 
 // Short slices (a block owns only a handful of tiles, as at 16K context on 256 compute units) use

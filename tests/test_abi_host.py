@@ -175,3 +175,16 @@ def test_spec_verify_argument_errors(lib):
     assert call(q=FAKE + 2) == h.ERR_BAD_ALIGN
     assert call(ws=FAKE + 64) == h.ERR_BAD_ALIGN
     assert call(ws_bytes=need - 1) == h.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_attention_append_argument_errors(lib):
+    kv = _kv()
+    for fn in (lib.hippo_verify_attention_append, lib.hippo_draft_attention_append):
+        def call(q=FAKE, kn=FAKE, vn=FAKE, k=FAKE, v=FAKE, out=FAKE, ws=FAKE, ws_bytes=1 << 30, q_len=6, ctx=16640):
+            return fn(q, q_len, kn, vn, k, v, C.byref(kv), ctx, 0.0, 0, out, None, ws, ws_bytes, None)
+        assert call(kn=None) == h.ERR_NULL_ARG
+        assert call(vn=None) == h.ERR_NULL_ARG
+        assert call(k=None) == h.ERR_NULL_ARG
+        assert call(kn=FAKE + 4) == h.ERR_BAD_ALIGN
+        assert call(q_len=0) == h.ERR_BAD_SHAPE
+        assert call(ws_bytes=64) == h.ERR_WORKSPACE_TOO_SMALL

@@ -154,3 +154,74 @@ def test_verify_full_size_large_share_sampled(hippo):
     for b in (0, 3):
         ro, _ = oracle.attention(x["q_new"][b:b + 1], x["k"][b:b + 1], x["v"][b:b + 1], cfg.ctx_len)
         assert_close(got[b:b + 1], ro, dt, "c5 batch %d" % b)
+
+
+# ---------------------------------------------------------------------------------------------
+# appended-row fusion: the new rows come from the projection's output and reach the cache in the
+# same launch
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("fn", ["verify", "draft"])
+@pytest.mark.parametrize("shape", [
+    # B, q_len, H, Hkv, d, ctx, num_splits
+    (1, 1, 4, 4, 64, 1, 0),
+    (2, 3, 8, 2, 64, 37, 0),
+    (1, 9, 7, 1, 128, 333, 4),       # new rows inside the last of four slices
+    (2, 6, 28, 4, 128, 2049, 0),     # the new rows straddle a tile boundary (2049 = 64 * 32 + 1)
+    (1, 12, 16, 2, 64, 515, 3),      # two row chunks
+    (1, 40, 4, 2, 64, 24, 2),        # more new rows than context: they span both slices
+    (1, 2, 6, 2, 64, 0, 0),          # empty context
+])
+def test_append_fusion(hippo, dtype, fn, shape):
+    B, ql, H, Hkv, d, ctx, ns = shape
+    q, k, v = rand_case(sum(shape), B, ql, H, Hkv, d, ctx, extra_rows=3)
+    q, k, v = prep(q, dtype), prep(k, dtype), prep(v, dtype)
+    f = hippo.hippo_verify_attention if fn == "verify" else hippo.hippo_draft_attention
+    # reference run: the new rows already in the cache
+    kd, vd = dev(k, dtype), dev(v, dtype)
+    want = f(dev(q, dtype), kd, vd, ctx, num_splits=ns)
+    # fused run: cache rows >= ctx hold garbage, the new rows arrive as [B, q_len, Hkv, d]
+    k_poison, v_poison = k.copy(), v.copy()
+    k_poison[:, :, ctx:] = 1e30
+    v_poison[:, :, ctx:] = -1e30
+    kc, vc = dev(k_poison, dtype), dev(v_poison, dtype)
+    k_new = dev(np.ascontiguousarray(k[:, :, ctx:ctx + ql].transpose(0, 2, 1, 3)), dtype)
+    v_new = dev(np.ascontiguousarray(v[:, :, ctx:ctx + ql].transpose(0, 2, 1, 3)), dtype)
+    got = f(dev(q, dtype), kc, vc, ctx, num_splits=ns, k_new=k_new, v_new=v_new)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)                        # same data through the same arithmetic
+    ro, _ = oracle.attention(q, k, v, ctx)
+    assert_close(host(got), ro, dtype, "append %s %s" % (fn, shape))
+    # the cache now holds the new rows, bit for bit; nothing else moved
+    np.testing.assert_array_equal(host(kc[:, :, :ctx + ql]), host(kd[:, :, :ctx + ql]))
+    np.testing.assert_array_equal(host(vc[:, :, :ctx + ql]), host(vd[:, :, :ctx + ql]))
+    np.testing.assert_array_equal(host(kc[:, :, ctx + ql:]), host(dev(k_poison, dtype)[:, :, ctx + ql:]))
+
+
+def test_append_fusion_decode_chain(hippo):
+    """Three consecutive verify calls at growing context, each appending its own rows: the third
+    sees what the first two wrote."""
+    cfg = si.CONFIGS["draft"]
+    x = si.make_inputs(cfg, 4)
+    dt, n = cfg.dtype, cfg.ctx_len
+    r = np.random.default_rng(0)
+    steps, ql = 3, 4
+    extra_k = prep(r.standard_normal((cfg.batch, cfg.n_kv_heads, steps * ql, cfg.head_dim)) / 8, dt)
+    extra_v = prep(r.standard_normal((cfg.batch, cfg.n_kv_heads, steps * ql, cfg.head_dim)) / 8, dt)
+    k_full = np.concatenate([x["k"][:, :, :n], extra_k], 2)
+    v_full = np.concatenate([x["v"][:, :, :n], extra_v], 2)
+    kc = dev(np.concatenate([x["k"][:, :, :n], np.zeros_like(extra_k)], 2), dt)
+    vc = dev(np.concatenate([x["v"][:, :, :n], np.zeros_like(extra_v)], 2), dt)
+    for s in range(steps):
+        ctx = n + s * ql
+        q = prep(r.standard_normal((cfg.batch, ql, cfg.n_q_heads, cfg.head_dim)), dt)
+        k_new = dev(np.ascontiguousarray(k_full[:, :, ctx:ctx + ql].transpose(0, 2, 1, 3)), dt)
+        v_new = dev(np.ascontiguousarray(v_full[:, :, ctx:ctx + ql].transpose(0, 2, 1, 3)), dt)
+        out = hippo.hippo_verify_attention(dev(q, dt), kc[:, :, :ctx + ql], vc[:, :, :ctx + ql], ctx, k_new=k_new,
+                                           v_new=v_new)
+        torch.cuda.synchronize()
+        ro, _ = oracle.attention(q, k_full[:, :, :ctx + ql], v_full[:, :, :ctx + ql], ctx)
+        assert_close(host(out), ro, dt, "chain step %d" % s)
+    np.testing.assert_array_equal(host(kc), prep(k_full, dt))
+    np.testing.assert_array_equal(host(vc), prep(v_full, dt))
