@@ -162,6 +162,28 @@ def main():
             h.hippo_verify_attention(qd[l], kd[l], vd[l], n_ctx, num_splits=args.num_splits, out=out_ver,
                                      workspace=ws_ver)
 
+    # paged cache: the same rows in 16-token pages scattered over a pool (one pool per layer)
+    PS = 16
+    n_pg = (n_tot + PS - 1) // PS
+    gen = torch.Generator(device="cpu").manual_seed(0)
+    tables = torch.stack([torch.randperm(B * n_pg, generator=gen)[:B * n_pg].reshape(B, n_pg) for _ in range(1)])[0]
+    table_d = tables.to(torch.int32).cuda()
+
+    def to_pool(x):                                   # [B, Hkv, N, d] -> [B * n_pg, PS, Hkv, d]
+        pad = torch.zeros((B, Hkv, n_pg * PS, d), dtype=x.dtype, device=x.device)
+        pad[:, :, :x.shape[2]] = x
+        pages = pad.permute(0, 2, 1, 3).reshape(B * n_pg, PS, Hkv, d).contiguous()
+        pool = torch.empty_like(pages)
+        pool[table_d.reshape(-1).long()] = pages
+        return pool
+    k_pool = [to_pool(kd[l]) for l in range(L)]
+    v_pool = [to_pool(vd[l]) for l in range(L)]
+
+    def verify_paged_all():
+        for l in range(L):
+            h.hippo_verify_attention_paged(qd[l], k_pool[l], v_pool[l], table_d, n_ctx, num_splits=args.num_splits,
+                                           out=out_ver, workspace=ws_ver)
+
     def score_only():
         h.hippo_score_tokens(q_txt, kd[0][:, :, :n_ctx], vid, scores_out=scores, workspace=ws_score)
 
@@ -207,6 +229,7 @@ def main():
     run_score = capture(score_only)
     run_verify_append = capture(verify_append_all)
     run_copy_verify = capture(copy_then_verify_all)
+    run_verify_paged = capture(verify_paged_all)
     run_sd_sampling = capture(spec_sampling)
     run_sd_greedy = capture(spec_greedy)
     torch.cuda.synchronize()
@@ -258,6 +281,7 @@ def main():
     t_prune_alone = alone(run_prune)
     t_verify_append = alone(run_verify_append) / L
     t_copy_verify = alone(run_copy_verify) / L
+    t_verify_paged = alone(run_verify_paged) / L
     t_sd_sampling = alone(run_sd_sampling) / SD_REPS
     t_sd_greedy = alone(run_sd_greedy) / SD_REPS
 
@@ -304,6 +328,7 @@ def main():
                "alone:prune": round(t_prune_alone * 1e6, 2),
                "alone:verify_with_fused_append_per_layer": round(t_verify_append * 1e6, 3),
                "alone:copy_new_rows_then_verify_per_layer": round(t_copy_verify * 1e6, 3),
+               "alone:verify_paged(16-token pages)_per_layer": round(t_verify_paged * 1e6, 3),
                "alone:spec_verify(sampling, V=%d)" % V: round(t_sd_sampling * 1e6, 2),
                "alone:spec_verify(greedy, V=%d)" % V: round(t_sd_greedy * 1e6, 2)},
         "verify_alone_GBps": round(kv_bytes / t_verify_alone / 1e9, 1),

@@ -201,6 +201,41 @@ int hippo_draft_attention_append(const void* q, int32_t q_len, const void* k_new
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same two attention calls over a PAGED cache (a cache-format variant for serving stacks that
+ * allocate the cache in fixed-size pages).  k_pool / v_pool are page pools; cache row n of sequence
+ * b and KV head hk lives at element
+ *     block_table[b * max_pages + n / page_size] * stride_page + (n % page_size) * stride_n + hk * stride_h
+ * (+ c for head-dim element c), e.g. a [n_pool_pages, page_size, H_kv, d] pool has stride_page =
+ * page_size * H_kv * d, stride_n = H_kv * d, stride_h = d.  block_table is a DEVICE array of int32,
+ * [B, max_pages]; entries outside [0, n_pool_pages) are clamped into the pool (the result is then
+ * meaningless, but no access leaves the pool).  page_size is a power of two, 16..256.  The result
+ * is bit-identical to the contiguous call on the same rows.  A block stages the page numbers of its
+ * KV slice in LDS, which bounds a slice to about 1000 pages: with num_splits forced very low on a
+ * long cache the call returns BAD_SHAPE.  Use hippo_workspace_bytes with a hippo_kv_desc of the same
+ * batch / heads / head_dim / dtype for the workspace size.
+ * Errors: as hippo_verify_attention, plus BAD_SHAPE for a page size, table width or pool size
+ * that does not fit, BAD_ALIGN for strides that break the 16-byte rule.
+ */
+typedef struct hippo_paged_kv_desc {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, dtype;
+  int32_t page_size;        /* tokens per page */
+  int32_t max_pages;        /* columns of block_table; >= ceil((ctx_len + q_len) / page_size) */
+  int32_t n_pool_pages;     /* pages in the pool */
+  int64_t stride_page, stride_n, stride_h;   /* elements */
+} hippo_paged_kv_desc;
+
+int hippo_verify_attention_paged(const void* q, int32_t q_len, const void* k_pool, const void* v_pool,
+                                 const int32_t* block_table, const hippo_paged_kv_desc* kv,
+                                 int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                                 void* out, float* lse_out,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+int hippo_draft_attention_paged(const void* q, int32_t q_len, const void* k_pool, const void* v_pool,
+                                const int32_t* block_table, const hippo_paged_kv_desc* kv,
+                                int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                                void* out, float* lse_out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Speculative-sampling verification of one chain of gamma draft tokens per sequence
  * (Preliminaries, "Speculative Decoding": Eq. 1, the resampling rule below it, and the extra token
  * after a full acceptance; Method, "Adaptive Decoding Strategy Switching": conservative mode

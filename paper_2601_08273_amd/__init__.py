@@ -21,6 +21,7 @@ OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO
 EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
            "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention",
            "hippo_verify_attention_append", "hippo_draft_attention_append",
+           "hippo_verify_attention_paged", "hippo_draft_attention_paged",
            "hippo_spec_verify_workspace_bytes", "hippo_spec_verify", "hippo_vpsd_prefill_buffer",
            "hippo_vpsd_init", "hippo_vpsd_plan", "hippo_vpsd_commit", "hippo_vpsd_simulate")
 VPSD_CONSERVATIVE, VPSD_OPTIMISTIC = 0, 1
@@ -42,6 +43,13 @@ class VpsdResult(C.Structure):
     _fields_ = [("time", C.c_double), ("speedup", C.c_double), ("n_emitted", C.c_int64), ("n_rounds", C.c_int64),
                 ("n_target_calls", C.c_int64), ("n_draft_tokens", C.c_int64), ("n_draft_wasted", C.c_int64),
                 ("n_mode_switches", C.c_int64), ("n_flags_used", C.c_int64)]
+
+
+class PagedKvDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("dtype", C.c_int32), ("page_size", C.c_int32),
+                ("max_pages", C.c_int32), ("n_pool_pages", C.c_int32),
+                ("stride_page", C.c_int64), ("stride_n", C.c_int64), ("stride_h", C.c_int64)]
 
 
 class KvDesc(C.Structure):
@@ -85,6 +93,9 @@ def load():
     lib.hippo_select_gather_kv.restype = C.c_int
     for fn in (lib.hippo_verify_attention, lib.hippo_draft_attention):
         fn.argtypes = [vp, i32, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
+        fn.restype = C.c_int
+    for fn in (lib.hippo_verify_attention_paged, lib.hippo_draft_attention_paged):
+        fn.argtypes = [vp, i32, vp, vp, vp, C.POINTER(PagedKvDesc), i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
     for fn in (lib.hippo_verify_attention_append, lib.hippo_draft_attention_append):
         fn.argtypes = [vp, i32, vp, vp, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
@@ -272,6 +283,43 @@ def hippo_draft_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: floa
                           want_lse: bool = False, out=None, workspace=None, stream=None, k_new=None, v_new=None):
     return _attention("hippo_draft_attention", CALL_DRAFT_ATTENTION, q, k_cache, v_cache, ctx_len,
                       softmax_scale, num_splits, want_lse, out, workspace, stream, k_new, v_new)
+
+
+def _attention_paged(fn_name, call, q, k_pool, v_pool, block_table, ctx_len, softmax_scale, num_splits, want_lse,
+                     out, workspace, stream):
+    torch = _torch()
+    lib = load()
+    assert q.is_contiguous() and q.dim() == 4 and k_pool.dim() == 4 and k_pool.stride(3) == 1
+    B, q_len, H, d = q.shape
+    n_pages, page_size, Hkv, _ = k_pool.shape
+    assert v_pool.shape == k_pool.shape and v_pool.stride() == k_pool.stride()
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous() and block_table.shape[0] == B
+    pd = PagedKvDesc(B, H, Hkv, d, _dtype_code(k_pool), page_size, block_table.shape[1], n_pages,
+                     k_pool.stride(0), k_pool.stride(1), k_pool.stride(2))
+    flat = KvDesc(B, H, Hkv, d, _dtype_code(k_pool), 0, k_pool.stride(2), k_pool.stride(1))
+    nbytes = workspace_bytes(call, flat, None, q_len, ctx_len + q_len, 0, num_splits)
+    ws = _workspace(nbytes, q.device, workspace)
+    if out is None:
+        out = torch.empty_like(q)
+    lse = torch.empty((B, H, q_len), dtype=torch.float32, device=q.device) if want_lse else None
+    st = getattr(lib, fn_name)(_ptr(q), q_len, _ptr(k_pool), _ptr(v_pool), _ptr(block_table), C.byref(pd), ctx_len,
+                               float(softmax_scale or 0.0), num_splits, _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
+                               _stream(stream))
+    _check(st, fn_name)
+    return (out, lse) if want_lse else out
+
+
+def hippo_verify_attention_paged(q, k_pool, v_pool, block_table, ctx_len: int, softmax_scale: float = 0.0,
+                                 num_splits: int = 0, want_lse: bool = False, out=None, workspace=None, stream=None):
+    """Pools [n_pages, page_size, Hkv, d]; block_table [B, max_pages] int32 on the device."""
+    return _attention_paged("hippo_verify_attention_paged", CALL_VERIFY_ATTENTION, q, k_pool, v_pool, block_table,
+                            ctx_len, softmax_scale, num_splits, want_lse, out, workspace, stream)
+
+
+def hippo_draft_attention_paged(q, k_pool, v_pool, block_table, ctx_len: int, softmax_scale: float = 0.0,
+                                num_splits: int = 0, want_lse: bool = False, out=None, workspace=None, stream=None):
+    return _attention_paged("hippo_draft_attention_paged", CALL_DRAFT_ATTENTION, q, k_pool, v_pool, block_table,
+                            ctx_len, softmax_scale, num_splits, want_lse, out, workspace, stream)
 
 
 def hippo_spec_verify(p_logits, q_logits, draft_tokens, u_accept, u_sample, temperature: float,

@@ -83,10 +83,23 @@ int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, in
   return HIPPO_OK;
 }
 
+// what the cache-format variants add to a plain attention call
+struct AttnExtra {
+  bool append = false;
+  const void* k_new = nullptr;
+  const void* v_new = nullptr;
+  const int32_t* block_table = nullptr;     // paged
+  int page_size = 0, max_pages = 0, n_pool_pages = 0;
+  long long page_stride = 0;
+};
+
 int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache, const void* v_cache,
                     const hippo_kv_desc* kv, int32_t ctx_len, float softmax_scale, int32_t num_splits,
                     void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream,
-                    bool append = false, const void* k_new = nullptr, const void* v_new = nullptr) {
+                    const AttnExtra& ex = AttnExtra()) {
+  const bool append = ex.append;
+  const void* k_new = ex.k_new;
+  const void* v_new = ex.v_new;
   if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr || workspace == nullptr)
     return HIPPO_ERR_NULL_ARG;
   if (append && (k_new == nullptr || v_new == nullptr)) return HIPPO_ERR_NULL_ARG;
@@ -101,6 +114,15 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   rc = plan_attention(call, kv, q_len, ctx_len + q_len, num_splits, &pl);
   if (rc != HIPPO_OK) return rc;
   if (workspace_bytes < pl.bytes) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
+  int page_shift = 0;
+  if (ex.block_table != nullptr) {
+    while ((1 << page_shift) < ex.page_size) ++page_shift;
+    // a block keeps the page numbers of its slice in LDS: bound the slice (32-token tiles, a ragged
+    // tile at either end) by the staging area
+    const long long tiles32 = ((long long)ctx_len + q_len + 31) / 32;
+    const long long slice_tokens = (tiles32 / pl.S + 2) * 32;
+    if (slice_tokens / ex.page_size + 2 > kMaxSlicePages) return HIPPO_ERR_BAD_SHAPE;
+  }
 
   AttnParams p;
   p.q = q; p.k = k_cache; p.v = v_cache; p.out = out; p.lse = lse_out;
@@ -116,6 +138,8 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks; p.variant = 0;
   p.k_new = append ? k_new : nullptr; p.v_new = append ? v_new : nullptr;
   p.k_w = const_cast<void*>(k_cache); p.v_w = const_cast<void*>(v_cache);
+  p.block_table = ex.block_table; p.page_shift = page_shift; p.max_pages = ex.max_pages;
+  p.n_pool_pages = ex.n_pool_pages; p.page_stride = ex.page_stride;
   const hipError_t e = launch_attention(p, kv->dtype, kv->head_dim, pl.mfma, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
 }
@@ -367,16 +391,68 @@ int hippo_verify_attention_append(const void* q, int32_t q_len, const void* k_ne
                                   void* k_cache, void* v_cache, const hippo_kv_desc* kv, int32_t ctx_len,
                                   float softmax_scale, int32_t num_splits, void* out, float* lse_out,
                                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (k_new == nullptr || v_new == nullptr) return HIPPO_ERR_NULL_ARG;
+  AttnExtra ex;
+  ex.append = true; ex.k_new = k_new; ex.v_new = v_new;
   return attention_entry(HIPPO_CALL_VERIFY_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
-                         num_splits, out, lse_out, workspace, workspace_bytes, stream, true, k_new, v_new);
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream, ex);
 }
 
 int hippo_draft_attention_append(const void* q, int32_t q_len, const void* k_new, const void* v_new,
                                  void* k_cache, void* v_cache, const hippo_kv_desc* kv, int32_t ctx_len,
                                  float softmax_scale, int32_t num_splits, void* out, float* lse_out,
                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (k_new == nullptr || v_new == nullptr) return HIPPO_ERR_NULL_ARG;
+  AttnExtra ex;
+  ex.append = true; ex.k_new = k_new; ex.v_new = v_new;
   return attention_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
-                         num_splits, out, lse_out, workspace, workspace_bytes, stream, true, k_new, v_new);
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream, ex);
+}
+
+// paged caches: translate the pool descriptor into the per-row strides the kernels use
+static int paged_entry(int call, const void* q, int32_t q_len, const void* k_pool, const void* v_pool,
+                       const int32_t* block_table, const hippo_paged_kv_desc* pd, int32_t ctx_len,
+                       float softmax_scale, int32_t num_splits, void* out, float* lse_out, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (pd == nullptr || block_table == nullptr) return HIPPO_ERR_NULL_ARG;
+  if (pd->page_size < 16 || pd->page_size > 256 || (pd->page_size & (pd->page_size - 1))) return HIPPO_ERR_BAD_SHAPE;
+  if (pd->n_pool_pages < 1 || pd->max_pages < 1 || ctx_len < 0 || q_len < 1) return HIPPO_ERR_BAD_SHAPE;
+  if (((long long)ctx_len + q_len + pd->page_size - 1) / pd->page_size > pd->max_pages) return HIPPO_ERR_BAD_SHAPE;
+  if (pd->n_kv_heads < 1 || pd->head_dim < 1 || pd->stride_n < pd->head_dim || pd->stride_h < 0)
+    return HIPPO_ERR_BAD_SHAPE;
+  // every element of a page lies inside the page's stride, so a clamped page number keeps every
+  // access inside the pool
+  if ((long long)(pd->page_size - 1) * pd->stride_n + (long long)(pd->n_kv_heads - 1) * pd->stride_h + pd->head_dim >
+      pd->stride_page)
+    return HIPPO_ERR_BAD_SHAPE;
+  if (reinterpret_cast<uintptr_t>(block_table) & 3u) return HIPPO_ERR_BAD_ALIGN;
+  hippo_kv_desc kv;
+  kv.batch = pd->batch; kv.n_q_heads = pd->n_q_heads; kv.n_kv_heads = pd->n_kv_heads;
+  kv.head_dim = pd->head_dim; kv.dtype = pd->dtype;
+  kv.stride_b = 0; kv.stride_h = pd->stride_h; kv.stride_n = pd->stride_n;
+  const int per16 = 16 / (pd->dtype == HIPPO_DTYPE_BF16 ? 2 : 4);
+  if (pd->stride_page % per16) return HIPPO_ERR_BAD_ALIGN;
+  AttnExtra ex;
+  ex.block_table = block_table; ex.page_size = pd->page_size; ex.max_pages = pd->max_pages;
+  ex.n_pool_pages = pd->n_pool_pages; ex.page_stride = pd->stride_page;
+  return attention_entry(call, q, q_len, k_pool, v_pool, &kv, ctx_len, softmax_scale, num_splits, out, lse_out,
+                         workspace, workspace_bytes, stream, ex);
+}
+
+int hippo_verify_attention_paged(const void* q, int32_t q_len, const void* k_pool, const void* v_pool,
+                                 const int32_t* block_table, const hippo_paged_kv_desc* kv, int32_t ctx_len,
+                                 float softmax_scale, int32_t num_splits, void* out, float* lse_out,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  return paged_entry(HIPPO_CALL_VERIFY_ATTENTION, q, q_len, k_pool, v_pool, block_table, kv, ctx_len,
+                     softmax_scale, num_splits, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+int hippo_draft_attention_paged(const void* q, int32_t q_len, const void* k_pool, const void* v_pool,
+                                const int32_t* block_table, const hippo_paged_kv_desc* kv, int32_t ctx_len,
+                                float softmax_scale, int32_t num_splits, void* out, float* lse_out,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  return paged_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_pool, v_pool, block_table, kv, ctx_len,
+                     softmax_scale, num_splits, out, lse_out, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

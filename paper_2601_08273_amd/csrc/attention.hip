@@ -116,6 +116,14 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
       if (n < p.n_total) {
         const T* ks = kbase + (long long)n * p.sn;
         const T* vs = vbase + (long long)n * p.sn;
+        if (p.block_table != nullptr) {                      // paged cache: page of row n, row inside it
+          int pg = p.block_table[(long long)b * p.max_pages + (n >> p.page_shift)];
+          pg = pg < 0 ? 0 : (pg >= p.n_pool_pages ? p.n_pool_pages - 1 : pg);
+          const long long o = (long long)pg * p.page_stride + (long long)(n & ((1 << p.page_shift) - 1)) * p.sn +
+                              (long long)hk * p.sh;
+          ks = (const T*)p.k + o;
+          vs = (const T*)p.v + o;
+        }
         if (p.k_new != nullptr && n >= p.ctx_len) {          // a row that has not reached the cache yet
           const long long o = (((long long)b * p.q_len + (n - p.ctx_len)) * p.Hkv + hk) * D;
           ks = (const T*)p.k_new + o;
@@ -274,8 +282,10 @@ struct GridSmem {
 };
 
 // TT = tokens per tile (16 or 32), NST = ring stages (super-tiles resident in LDS)
-template <int D, int RB, int TG, int TT, int NST, bool APPEND>
+// MODE: 0 = contiguous cache, 1 = contiguous cache with appended-row fusion, 2 = paged cache
+template <int D, int RB, int TG, int TT, int NST, int MODE>
 __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) {
+  constexpr bool APPEND = MODE == 1, PAGED = MODE == 2;
   using SM = GridSmem<D, TG, TT, NST>;
   constexpr int WAVES = RB * TG;
   constexpr int KS = D / 32;
@@ -311,8 +321,9 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 
   const unsigned ring_addr = (unsigned)(uintptr_t)ring;
   const unsigned q_addr = (unsigned)(uintptr_t)Qs;
-  const char* kbase = (const char*)p.k + ((long long)b * p.sb + (long long)hk * p.sh) * 2;
-  const char* vbase = (const char*)p.v + ((long long)b * p.sb + (long long)hk * p.sh) * 2;
+  // paged: the pools' base plus the head offset; the page and the row inside it are added per transfer
+  const char* kbase = (const char*)p.k + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * 2;
+  const char* vbase = (const char*)p.v + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * 2;
   const long long row_bytes = p.sn * 2;
   const int ld_row = lane / CPR, ld_pc = lane % CPR;
 
@@ -327,6 +338,20 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   // tiles past the block's range and rows past the cache's end re-read the block's last valid row
   // (a cache hit), so every super-tile costs every issuer exactly PER transfers
   const long long row_cap = ((long long)t_hi * TT < p.n_total ? (long long)t_hi * TT : p.n_total) - 1;
+  // paged: the page numbers of the rows this block streams, staged in LDS once (table entries
+  // outside the pool are clamped into it, so a bad table cannot send a transfer out of bounds)
+  int* page_s = (int*)(smem + SM::total(RB));
+  const long long page_mask = PAGED ? (1ll << p.page_shift) - 1 : 0;
+  const int slot_lo = PAGED ? (int)(((long long)t_lo * TT) >> p.page_shift) : 0;
+  if (PAGED) {
+    const int n_slots = n_blk > 0 ? (int)(row_cap >> p.page_shift) - slot_lo + 1 : 0;
+    for (int i = tid; i < n_slots && i < kMaxSlicePages; i += RB * TG * 64) {
+      int pg = p.block_table[(long long)b * p.max_pages + slot_lo + i];
+      pg = pg < 0 ? 0 : (pg >= p.n_pool_pages ? p.n_pool_pages - 1 : pg);
+      page_s[i] = pg;
+    }
+    __syncthreads();
+  }
   auto issue_super = [&](int si) {
     const unsigned dst = ring_addr + (si % NST) * SM::kSuperBytes;
     const int tile0 = t_lo + si * TG;
@@ -338,6 +363,9 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       long long row = (long long)(tile0 + tt) * TT + r;
       row = row < row_cap ? row : row_cap;
       const char* src = (which ? vbase : kbase) + row * row_bytes;
+      if (PAGED)
+        src = (which ? vbase : kbase) + ((long long)page_s[(int)(row >> p.page_shift) - slot_lo] * p.page_stride +
+                                         (row & page_mask) * p.sn) * 2;
       if (APPEND && row >= p.ctx_len)                      // a row that has not reached the cache yet
         src = (const char*)(which ? p.v_new : p.k_new) +
               ((((long long)b * p.q_len + (row - p.ctx_len)) * p.Hkv + hk) * D) * 2;
@@ -624,26 +652,29 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
 // =================================================================================================
 // host launch
 // =================================================================================================
-template <int D, int RB, int TG, int TT, int NST, bool APPEND>
-static hipError_t launch_grid_ap(const AttnParams& p, hipStream_t st) {
-  constexpr int smem = GridSmem<D, TG, TT, NST>::total(RB);
+template <int D, int RB, int TG, int TT, int NST, int MODE>
+static hipError_t launch_grid_mode(const AttnParams& p, hipStream_t st) {
+  // the paged variant keeps its slice of the page table behind the ring
+  constexpr int smem = GridSmem<D, TG, TT, NST>::total(RB) + (MODE == 2 ? kMaxSlicePages * 4 : 0);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, APPEND>,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, MODE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid(p.S, p.Hkv, p.B * p.n_chunks);
-  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, APPEND>), grid, dim3(RB * TG * 64), smem, st, p);
+  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE>), grid, dim3(RB * TG * 64), smem, st, p);
   return hipGetLastError();
 }
 
-// the appended-row variant is a separate instantiation, so the plain call carries none of its selects
+// the appended-row and paged variants are separate instantiations, so the plain call carries none of
+// their address selects
 template <int D, int RB, int TG, int TT, int NST>
 static hipError_t launch_grid(const AttnParams& p, hipStream_t st) {
-  return p.k_new != nullptr ? launch_grid_ap<D, RB, TG, TT, NST, true>(p, st)
-                            : launch_grid_ap<D, RB, TG, TT, NST, false>(p, st);
+  if (p.block_table != nullptr) return launch_grid_mode<D, RB, TG, TT, NST, 2>(p, st);
+  if (p.k_new != nullptr) return launch_grid_mode<D, RB, TG, TT, NST, 1>(p, st);
+  return launch_grid_mode<D, RB, TG, TT, NST, 0>(p, st);
 }
 
 // Short slices (a block owns only a handful of tiles, as at 16K context on 256 compute units) use

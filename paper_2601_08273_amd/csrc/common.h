@@ -108,7 +108,13 @@ struct AttnParams {
   const void* v_new;
   void* k_w;              // the caches again, writable
   void* v_w;
+  // paged cache: when block_table is set, k / v point at page pools and cache row n of sequence b,
+  // KV head hk lives at ((table[b][n >> page_shift] * page_stride) + (n & mask) * sn + hk * sh)
+  const int32_t* block_table;   // [B, max_pages]
+  int page_shift, max_pages, n_pool_pages;
+  long long page_stride;        // elements
 };
+constexpr int kMaxSlicePages = 1024;   // page-table entries a block stages in LDS
 
 // Launchers, one per translation unit.  All return a hipError_t from hipGetLastError().
 hipError_t launch_attention(const AttnParams& p, int dtype, int head_dim, bool use_mfma, hipStream_t st);

@@ -188,3 +188,31 @@ def test_attention_append_argument_errors(lib):
         assert call(kn=FAKE + 4) == h.ERR_BAD_ALIGN
         assert call(q_len=0) == h.ERR_BAD_SHAPE
         assert call(ws_bytes=64) == h.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_attention_paged_argument_errors(lib):
+    def desc(**kw):
+        d = dict(batch=1, n_q_heads=28, n_kv_heads=4, head_dim=128, dtype=h.DTYPE_BF16, page_size=16, max_pages=1100,
+                 n_pool_pages=2000, stride_page=16 * 4 * 128, stride_n=4 * 128, stride_h=128)
+        d.update(kw)
+        return h.PagedKvDesc(**d)
+
+    def call(pd=None, q=FAKE, k=FAKE, v=FAKE, table=FAKE, ctx=16640, q_len=6, splits=0, ws_bytes=1 << 30,
+             fn=lib.hippo_verify_attention_paged):
+        pd = pd or desc()
+        return fn(q, q_len, k, v, table, C.byref(pd), ctx, 0.0, splits, FAKE, None, FAKE, ws_bytes, None)
+    for fn in (lib.hippo_verify_attention_paged, lib.hippo_draft_attention_paged):
+        assert call(table=None, fn=fn) == h.ERR_NULL_ARG
+        assert call(k=None, fn=fn) == h.ERR_NULL_ARG
+        assert call(desc(page_size=24), fn=fn) == h.ERR_BAD_SHAPE          # not a power of two
+        assert call(desc(page_size=8), fn=fn) == h.ERR_BAD_SHAPE
+        assert call(desc(max_pages=100), fn=fn) == h.ERR_BAD_SHAPE         # table too narrow for the cache
+        assert call(desc(stride_page=1000), fn=fn) == h.ERR_BAD_SHAPE      # pages overlap
+        assert call(desc(stride_page=16 * 4 * 128 + 4), fn=fn) == h.ERR_BAD_ALIGN
+        assert call(desc(dtype=9), fn=fn) == h.ERR_BAD_DTYPE
+        assert call(table=FAKE + 2, fn=fn) == h.ERR_BAD_ALIGN
+        assert call(ws_bytes=64, fn=fn) == h.ERR_WORKSPACE_TOO_SMALL
+    # one slice over 16.6K tokens of 16-token pages does not fit the page staging area
+    assert call(splits=1) == h.ERR_BAD_SHAPE
+    assert lib.hippo_verify_attention_paged(FAKE, 6, FAKE, FAKE, FAKE, None, 10, 0.0, 0, FAKE, None, FAKE, 1 << 20,
+                                            None) == h.ERR_NULL_ARG

@@ -225,3 +225,74 @@ def test_append_fusion_decode_chain(hippo):
         assert_close(host(out), ro, dt, "chain step %d" % s)
     np.testing.assert_array_equal(host(kc), prep(k_full, dt))
     np.testing.assert_array_equal(host(vc), prep(v_full, dt))
+
+
+# ---------------------------------------------------------------------------------------------
+# paged cache: the same rows scattered over a page pool
+# ---------------------------------------------------------------------------------------------
+
+def to_pages(x, page_size, n_pool, rng):
+    """[B, Hkv, N, d] -> (pool [n_pool, page_size, Hkv, d], table [B, max_pages]); pages in random
+    pool slots, unused slots and the tail of the last page filled with garbage."""
+    B, Hkv, N, d = x.shape
+    max_pages = (N + page_size - 1) // page_size
+    assert B * max_pages <= n_pool
+    slots = rng.permutation(n_pool)[:B * max_pages].reshape(B, max_pages).astype(np.int32)
+    pool = np.full((n_pool, page_size, Hkv, d), 3e4, dtype=np.float32)
+    for b in range(B):
+        for pg in range(max_pages):
+            rows = x[b, :, pg * page_size:(pg + 1) * page_size]          # [Hkv, <=page, d]
+            pool[slots[b, pg], :rows.shape[1]] = rows.transpose(1, 0, 2)
+    return pool, slots
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("shape", [
+    # B, q_len, H, Hkv, d, ctx, page_size, num_splits
+    (1, 1, 4, 4, 64, 1, 16, 0),
+    (2, 3, 8, 2, 64, 37, 16, 0),
+    (1, 9, 7, 1, 128, 333, 32, 4),
+    (2, 6, 28, 4, 128, 2049, 64, 0),      # headline head geometry
+    (1, 12, 16, 2, 64, 515, 256, 3),      # pages larger than a slice
+    (1, 6, 28, 4, 128, 5000, 16, 0),      # many small pages
+    (1, 2, 6, 2, 64, 0, 16, 0),           # empty context
+])
+def test_paged_cache(hippo, dtype, shape):
+    B, ql, H, Hkv, d, ctx, ps, ns = shape
+    q, k, v = rand_case(sum(shape), B, ql, H, Hkv, d, ctx)
+    q, k, v = prep(q, dtype), prep(k, dtype), prep(v, dtype)
+    rng = np.random.default_rng(7)
+    n_pool = B * ((ctx + ql + ps - 1) // ps) + 5
+    k_pool, table = to_pages(k, ps, n_pool, rng)
+    v_pool, _ = to_pages(v, ps, n_pool, np.random.default_rng(7))        # same slots
+    for fn, plain, paged in (("verify", hippo.hippo_verify_attention, hippo.hippo_verify_attention_paged),
+                             ("draft", hippo.hippo_draft_attention, hippo.hippo_draft_attention_paged)):
+        want, want_lse = plain(dev(q, dtype), dev(k, dtype), dev(v, dtype), ctx, num_splits=ns, want_lse=True)
+        got, got_lse = paged(dev(q, dtype), dev(k_pool, dtype), dev(v_pool, dtype), torch.from_numpy(table).cuda(),
+                             ctx, num_splits=ns, want_lse=True)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want) and torch.equal(got_lse, want_lse), (fn, shape)
+    ro, _ = oracle.attention(q, k, v, ctx)
+    assert_close(host(got), ro, dtype, "paged %s" % (shape,))
+
+
+def test_paged_cache_full_size(hippo):
+    """The 16K headline configuration through 16-token pages, in the heuristic's own launch shape."""
+    cfg = si.CONFIGS["c3_16k"]
+    x = si.make_inputs(cfg, 0)
+    dt, n = cfg.dtype, cfg.ctx_len
+    rng = np.random.default_rng(1)
+    n_pool = (n + cfg.q_len + 15) // 16 + 9
+    k_pool, table = to_pages(prep(x["k"], dt), 16, n_pool, rng)
+    v_pool, _ = to_pages(prep(x["v"], dt), 16, n_pool, np.random.default_rng(1))
+    q = dev(x["q_new"], dt)
+    want = hippo.hippo_verify_attention(q, dev(x["k"], dt), dev(x["v"], dt), n)
+    got = hippo.hippo_verify_attention_paged(q, dev(k_pool, dt), dev(v_pool, dt), torch.from_numpy(table).cuda(), n)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    # a table entry outside the pool is clamped into it: garbage out, but no access leaves the pool
+    bad = table.copy()
+    bad[0, 3] = 10 ** 9
+    bad[0, 4] = -5
+    hippo.hippo_verify_attention_paged(q, dev(k_pool, dt), dev(v_pool, dt), torch.from_numpy(bad).cuda(), n)
+    torch.cuda.synchronize()
