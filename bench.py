@@ -26,6 +26,7 @@ kernels and the CPU oracle timed on the host cores (a reported baseline, not a t
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -184,6 +185,24 @@ def main():
             h.hippo_verify_attention_paged(qd[l], k_pool[l], v_pool[l], table_d, n_ctx, num_splits=args.num_splits,
                                            out=out_ver, workspace=ws_ver)
 
+    # Eq. 2 summed over several layers: one call that sweeps them in shared launches, versus one
+    # accumulate call per layer
+    NLS = min(4, L)
+    ws_layers = torch.empty(h.load().hippo_score_layers_workspace_bytes(C.byref(kvd), C.byref(vid), cfg.l_txt, NLS),
+                            dtype=torch.uint8, device="cuda")
+    mass = torch.zeros((B, cfg.n_visual), dtype=torch.float32, device="cuda")
+    k_ctx = [kd[l][:, :, :n_ctx] for l in range(NLS)]
+
+    def score_layers_one_call():
+        h.hippo_score_tokens_layers([q_txt] * NLS, k_ctx, vid, emb_layer=NLS - 1, scores_out=scores, workspace=ws_layers)
+
+    def score_layers_accumulate():
+        mass.zero_()
+        for l in range(NLS - 1):
+            h.hippo_score_tokens(q_txt, k_ctx[l], vid, flags=h.SCORE_ACCUMULATE_ONLY, attn_mass_inout=mass,
+                                 workspace=ws_score)
+        h.hippo_score_tokens(q_txt, k_ctx[NLS - 1], vid, attn_mass_inout=mass, scores_out=scores, workspace=ws_score)
+
     def score_only():
         h.hippo_score_tokens(q_txt, kd[0][:, :, :n_ctx], vid, scores_out=scores, workspace=ws_score)
 
@@ -230,6 +249,8 @@ def main():
     run_verify_append = capture(verify_append_all)
     run_copy_verify = capture(copy_then_verify_all)
     run_verify_paged = capture(verify_paged_all)
+    run_layers_one = capture(score_layers_one_call)
+    run_layers_acc = capture(score_layers_accumulate)
     run_sd_sampling = capture(spec_sampling)
     run_sd_greedy = capture(spec_greedy)
     torch.cuda.synchronize()
@@ -282,6 +303,8 @@ def main():
     t_verify_append = alone(run_verify_append) / L
     t_copy_verify = alone(run_copy_verify) / L
     t_verify_paged = alone(run_verify_paged) / L
+    t_layers_one = alone(run_layers_one)
+    t_layers_acc = alone(run_layers_acc)
     t_sd_sampling = alone(run_sd_sampling) / SD_REPS
     t_sd_greedy = alone(run_sd_greedy) / SD_REPS
 
@@ -329,6 +352,8 @@ def main():
                "alone:verify_with_fused_append_per_layer": round(t_verify_append * 1e6, 3),
                "alone:copy_new_rows_then_verify_per_layer": round(t_copy_verify * 1e6, 3),
                "alone:verify_paged(16-token pages)_per_layer": round(t_verify_paged * 1e6, 3),
+               "alone:score_%d_layers(one call)" % NLS: round(t_layers_one * 1e6, 2),
+               "alone:score_%d_layers(accumulate calls)" % NLS: round(t_layers_acc * 1e6, 2),
                "alone:spec_verify(sampling, V=%d)" % V: round(t_sd_sampling * 1e6, 2),
                "alone:spec_verify(greedy, V=%d)" % V: round(t_sd_greedy * 1e6, 2)},
         "verify_alone_GBps": round(kv_bytes / t_verify_alone / 1e9, 1),

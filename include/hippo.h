@@ -125,6 +125,26 @@ int hippo_score_tokens(const void* q_txt, int32_t l_txt,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same with Eq. 2's outer sum over layers done inside the call: the attention term is
+ * sum over the n_layers given layers of that layer's s_attn (queries and keys of layer l from
+ * q_txt_layers[l], k_cache_layers[l]; all layers share kv's shape and strides), swept in ONE launch per
+ * pass instead of one call per layer.  q_txt_layers and k_cache_layers are HOST arrays of n_layers
+ * device pointers (1 <= n_layers <= 64), read before the call returns.  When emb is NULL the
+ * embedding terms use the keys of layer emb_layer.  attn_mass_inout, if given, is added to (and
+ * updated with) the call's layer sum, exactly as for single calls.  hippo_score_tokens is this call
+ * with one layer.  Workspace: hippo_score_layers_workspace_bytes(kv, vid, l_txt, n_layers).
+ */
+size_t hippo_score_layers_workspace_bytes(const hippo_kv_desc* kv, const hippo_video_desc* vid,
+                                          int32_t l_txt, int32_t n_layers);
+int hippo_score_tokens_layers(int32_t n_layers, const void* const* q_txt_layers, int32_t l_txt,
+                              const void* const* k_cache_layers, int32_t emb_layer,
+                              const hippo_kv_desc* kv, int32_t seq_len, const hippo_video_desc* vid,
+                              const void* emb, int32_t emb_dim, int64_t emb_stride_tok,
+                              uint32_t flags,
+                              float* attn_mass_inout, float* scores_out, float* components_out,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Top-k retention and draft-cache construction (Method, end of "Holistic Score Fusion": keep the
  * top-k visual tokens by score; App. "Details of Experimental Setups": the pruned video features
  * are removed from the draft model's input, everything that is not video is kept whole).

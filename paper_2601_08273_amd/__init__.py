@@ -19,6 +19,7 @@ SCORE_ATTN, SCORE_TEMP, SCORE_SPA, SCORE_ALL, SCORE_ACCUMULATE_ONLY = 1, 2, 4, 7
 OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = range(7)
 
 EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
+           "hippo_score_layers_workspace_bytes", "hippo_score_tokens_layers",
            "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention",
            "hippo_verify_attention_append", "hippo_draft_attention_append",
            "hippo_verify_attention_paged", "hippo_draft_attention_paged",
@@ -89,6 +90,11 @@ def load():
     lib.hippo_workspace_bytes.restype = sz
     lib.hippo_score_tokens.argtypes = [vp, i32, vp, kvp, i32, vdp, vp, i32, i64, u32, vp, vp, vp, vp, sz, vp]
     lib.hippo_score_tokens.restype = C.c_int
+    lib.hippo_score_layers_workspace_bytes.argtypes = [kvp, vdp, i32, i32]
+    lib.hippo_score_layers_workspace_bytes.restype = C.c_size_t
+    lib.hippo_score_tokens_layers.argtypes = [i32, vp, i32, vp, i32, kvp, i32, vdp, vp, i32, i64, u32, vp, vp, vp, vp,
+                                              sz, vp]
+    lib.hippo_score_tokens_layers.restype = C.c_int
     lib.hippo_select_gather_kv.argtypes = [vp, i32, vp, vp, kvp, i32, vdp, vp, vp, kvp, vp, vp, sz, vp]
     lib.hippo_select_gather_kv.restype = C.c_int
     for fn in (lib.hippo_verify_attention, lib.hippo_draft_attention):
@@ -206,6 +212,39 @@ def hippo_score_tokens(q_txt, k_cache, vid: VideoDesc, emb=None, flags: int = SC
                                 _ptr(emb), emb_dim, emb_stride, flags, _ptr(attn_mass_inout), _ptr(scores),
                                 _ptr(comps), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "hippo_score_tokens")
+    return (scores, comps) if want_components else scores
+
+
+def hippo_score_tokens_layers(q_txt_layers, k_cache_layers, vid: VideoDesc, emb_layer: int = 0, emb=None,
+                              flags: int = SCORE_ALL, attn_mass_inout=None, want_components: bool = False,
+                              scores_out=None, workspace=None, stream=None):
+    """Eq. 2 with its sum over layers inside one call: lists of per-layer q_txt [B,L,H,d] and
+    k_cache [B,Hkv,N,d] (same shapes and strides) -> scores [B,N_v] fp32 (and components)."""
+    torch = _torch()
+    lib = load()
+    n_layers = len(q_txt_layers)
+    assert n_layers == len(k_cache_layers) and n_layers >= 1
+    q0, k0 = q_txt_layers[0], k_cache_layers[0]
+    B, L, H, d = q0.shape
+    for q, k in zip(q_txt_layers, k_cache_layers):
+        assert q.is_contiguous() and q.shape == q0.shape and k.shape == k0.shape and k.stride() == k0.stride()
+    kv = kv_desc(k0, H)
+    n_vis = vid.n_frames * vid.grid_h * vid.grid_w
+    nbytes = int(lib.hippo_score_layers_workspace_bytes(C.byref(kv), C.byref(vid), L, n_layers))
+    ws = _workspace(nbytes, q0.device, workspace)
+    acc_only = bool(flags & SCORE_ACCUMULATE_ONLY)
+    scores = scores_out
+    if scores is None and not acc_only:
+        scores = torch.empty((B, n_vis), dtype=torch.float32, device=q0.device)
+    comps = torch.zeros((3, B, n_vis), dtype=torch.float32, device=q0.device) if want_components else None
+    emb_dim, emb_stride = (0, 0) if emb is None else (emb.shape[2], emb.stride(1))
+    qs = (C.c_void_p * n_layers)(*[q.data_ptr() for q in q_txt_layers])
+    ks = (C.c_void_p * n_layers)(*[k.data_ptr() for k in k_cache_layers])
+    st = lib.hippo_score_tokens_layers(n_layers, C.cast(qs, C.c_void_p), L, C.cast(ks, C.c_void_p), emb_layer,
+                                       C.byref(kv), k0.shape[2], C.byref(vid), _ptr(emb), emb_dim, emb_stride, flags,
+                                       _ptr(attn_mass_inout), _ptr(scores), _ptr(comps), _ptr(ws), ws.numel(),
+                                       _stream(stream))
+    _check(st, "hippo_score_tokens_layers")
     return (scores, comps) if want_components else scores
 
 

@@ -150,18 +150,19 @@ struct ScorePlan {
   size_t off_row_l, off_row_lse, off_col, off_sa, off_st, off_ss, bytes;
 };
 
-int plan_score(const hippo_kv_desc* kv, const hippo_video_desc* vid, int l_txt, ScorePlan* pl) {
+int plan_score(const hippo_kv_desc* kv, const hippo_video_desc* vid, int l_txt, int n_layers, ScorePlan* pl) {
   if (l_txt < 1 || l_txt > (1 << 20)) return HIPPO_ERR_BAD_SHAPE;
+  if (n_layers < 1 || n_layers > kMaxScoreLayers || (long long)kv->batch * n_layers > 65535) return HIPPO_ERR_BAD_SHAPE;
   const long long Nv = (long long)vid->n_frames * vid->grid_h * vid->grid_w;
   const int tile = score_token_tile(kv->dtype);
   pl->n_tile = (int)((Nv + tile - 1) / tile);
   if (pl->n_tile > 0x7fffffff / 2) return HIPPO_ERR_BAD_SHAPE;
-  const size_t rows = (size_t)kv->batch * kv->n_q_heads * l_txt;
+  const size_t rows = (size_t)kv->batch * n_layers * kv->n_q_heads * l_txt;
   const size_t row_part = align_up(rows * pl->n_tile * sizeof(float), 256);
   const size_t row_lse = align_up(rows * sizeof(float), 256);
-  pl->n_rsplit = score_row_splits(kv->dtype, (long long)pl->n_tile * kv->n_kv_heads * kv->batch,
+  pl->n_rsplit = score_row_splits(kv->dtype, (long long)pl->n_tile * kv->n_kv_heads * kv->batch * n_layers,
                                   l_txt * (kv->n_q_heads / kv->n_kv_heads));
-  const size_t col = align_up((size_t)kv->batch * kv->n_kv_heads * pl->n_rsplit * Nv * sizeof(float), 256);
+  const size_t col = align_up((size_t)kv->batch * n_layers * kv->n_kv_heads * pl->n_rsplit * Nv * sizeof(float), 256);
   const size_t vec = align_up((size_t)kv->batch * Nv * sizeof(float), 256);
   size_t o = 0;
   o += row_part;            pl->off_row_l = o;
@@ -223,7 +224,7 @@ size_t hippo_workspace_bytes(int32_t call, const hippo_kv_desc* kv, const hippo_
   switch (call) {
     case HIPPO_CALL_SCORE_TOKENS: {
       ScorePlan pl;
-      if (check_video(vid) != HIPPO_OK || plan_score(kv, vid, n_rows, &pl) != HIPPO_OK) return 0;
+      if (check_video(vid) != HIPPO_OK || plan_score(kv, vid, n_rows, 1, &pl) != HIPPO_OK) return 0;
       return pl.bytes;
     }
     case HIPPO_CALL_SELECT_GATHER_KV:
@@ -239,11 +240,23 @@ size_t hippo_workspace_bytes(int32_t call, const hippo_kv_desc* kv, const hippo_
   }
 }
 
-int hippo_score_tokens(const void* q_txt, int32_t l_txt, const void* k_cache, const hippo_kv_desc* kv,
-                       int32_t seq_len, const hippo_video_desc* vid, const void* emb, int32_t emb_dim,
-                       int64_t emb_stride_tok, uint32_t flags, float* attn_mass_inout, float* scores_out,
-                       float* components_out, void* workspace, size_t workspace_bytes, void* stream) {
-  if (q_txt == nullptr || k_cache == nullptr || workspace == nullptr) return HIPPO_ERR_NULL_ARG;
+size_t hippo_score_layers_workspace_bytes(const hippo_kv_desc* kv, const hippo_video_desc* vid, int32_t l_txt,
+                                          int32_t n_layers) {
+  ScorePlan pl;
+  if (check_kv(kv) != HIPPO_OK || check_video(vid) != HIPPO_OK || plan_score(kv, vid, l_txt, n_layers, &pl) != HIPPO_OK)
+    return 0;
+  return pl.bytes;
+}
+
+int hippo_score_tokens_layers(int32_t n_layers, const void* const* q_txt_layers, int32_t l_txt,
+                              const void* const* k_cache_layers, int32_t emb_layer, const hippo_kv_desc* kv,
+                              int32_t seq_len, const hippo_video_desc* vid, const void* emb, int32_t emb_dim,
+                              int64_t emb_stride_tok, uint32_t flags, float* attn_mass_inout, float* scores_out,
+                              float* components_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (q_txt_layers == nullptr || k_cache_layers == nullptr || workspace == nullptr) return HIPPO_ERR_NULL_ARG;
+  if (n_layers < 1 || n_layers > kMaxScoreLayers || emb_layer < 0 || emb_layer >= n_layers) return HIPPO_ERR_BAD_SHAPE;
+  for (int l = 0; l < n_layers; ++l)
+    if (q_txt_layers[l] == nullptr || k_cache_layers[l] == nullptr) return HIPPO_ERR_NULL_ARG;
   int rc = check_kv(kv);
   if (rc != HIPPO_OK) return rc;
   if ((rc = check_video(vid)) != HIPPO_OK) return rc;
@@ -261,14 +274,20 @@ int hippo_score_tokens(const void* q_txt, int32_t l_txt, const void* k_cache, co
     if (emb_dim % per16) return HIPPO_ERR_BAD_SHAPE;
     if (emb_stride_tok % per16 || !aligned16(emb)) return HIPPO_ERR_BAD_ALIGN;
   }
-  if (!aligned16(q_txt) || !aligned16(k_cache) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
-    return HIPPO_ERR_BAD_ALIGN;
+  for (int l = 0; l < n_layers; ++l)
+    if (!aligned16(q_txt_layers[l]) || !aligned16(k_cache_layers[l])) return HIPPO_ERR_BAD_ALIGN;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HIPPO_ERR_BAD_ALIGN;
   ScorePlan pl;
-  if ((rc = plan_score(kv, vid, l_txt, &pl)) != HIPPO_OK) return rc;
+  if ((rc = plan_score(kv, vid, l_txt, n_layers, &pl)) != HIPPO_OK) return rc;
   if (workspace_bytes < pl.bytes) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
 
   ScoreParams p;
-  p.q_txt = q_txt; p.k_cache = k_cache; p.emb = emb;
+  p.q_txt = q_txt_layers[0]; p.k_cache = k_cache_layers[emb_layer]; p.emb = emb;
+  p.n_layers = n_layers; p.Bz = kv->batch * n_layers;
+  for (int l = 0; l < kMaxScoreLayers; ++l) {
+    p.q_layers[l] = l < n_layers ? q_txt_layers[l] : nullptr;
+    p.k_layers[l] = l < n_layers ? k_cache_layers[l] : nullptr;
+  }
   p.B = kv->batch; p.L = l_txt; p.H = kv->n_q_heads; p.Hkv = kv->n_kv_heads;
   p.G = kv->n_q_heads / kv->n_kv_heads; p.D = kv->head_dim; p.dtype = kv->dtype;
   p.sb = kv->stride_b; p.sh = kv->stride_h; p.sn = kv->stride_n;
@@ -289,6 +308,17 @@ int hippo_score_tokens(const void* q_txt, int32_t l_txt, const void* k_cache, co
   p.n_rsplit = pl.n_rsplit;
   const hipError_t e = launch_score(p, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
+}
+
+int hippo_score_tokens(const void* q_txt, int32_t l_txt, const void* k_cache, const hippo_kv_desc* kv,
+                       int32_t seq_len, const hippo_video_desc* vid, const void* emb, int32_t emb_dim,
+                       int64_t emb_stride_tok, uint32_t flags, float* attn_mass_inout, float* scores_out,
+                       float* components_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (q_txt == nullptr || k_cache == nullptr) return HIPPO_ERR_NULL_ARG;
+  const void* qs[1] = {q_txt};
+  const void* ks[1] = {k_cache};
+  return hippo_score_tokens_layers(1, qs, l_txt, ks, 0, kv, seq_len, vid, emb, emb_dim, emb_stride_tok, flags,
+                                   attn_mass_inout, scores_out, components_out, workspace, workspace_bytes, stream);
 }
 
 int hippo_select_gather_kv(const float* scores, int32_t k, const void* k_src, const void* v_src,

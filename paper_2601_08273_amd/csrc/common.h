@@ -119,9 +119,15 @@ constexpr int kMaxSlicePages = 1024;   // page-table entries a block stages in L
 // Launchers, one per translation unit.  All return a hipError_t from hipGetLastError().
 hipError_t launch_attention(const AttnParams& p, int dtype, int head_dim, bool use_mfma, hipStream_t st);
 
+constexpr int kMaxScoreLayers = 64;   // layers whose s_attn sweeps can share one launch
+
 struct ScoreParams {
-  const void* q_txt;
-  const void* k_cache;
+  const void* q_txt;      // layer 0's (kept for the single-layer kernels)
+  const void* k_cache;    // the cache whose keys act as the embedding when emb is null
+  int n_layers;           // layers swept by this call (Eq. 2's outer sum)
+  int Bz;                 // B * n_layers: (layer, batch element) pairs, the s_attn kernels' "batch"
+  const void* q_layers[kMaxScoreLayers];   // [B, L, H, D] per layer
+  const void* k_layers[kMaxScoreLayers];   // caches per layer (same strides)
   const void* emb;       // null => keys concatenated over KV heads
   int B, L, H, Hkv, G, D, dtype;
   long long sb, sh, sn;
@@ -133,10 +139,10 @@ struct ScoreParams {
   float* scores_out;
   float* components_out;
   // workspace pieces
-  float* row_m;      // [n_tile, B, Hkv, L*G] partial row maxima (row r = i*G + g of a KV head)
-  float* row_l;      // [n_tile, B, Hkv, L*G] partial row sums
-  float* row_lse;    // [B, Hkv, L*G] final log2-domain row normaliser
-  float* col_part;   // [B, Hkv * n_rsplit, Nv] column sums per KV head and row run
+  float* row_m;      // [n_tile, Bz, Hkv, L*G] partial row maxima (row r = i*G + g of a KV head)
+  float* row_l;      // [n_tile, Bz, Hkv, L*G] partial row sums
+  float* row_lse;    // [Bz, Hkv, L*G] final log2-domain row normaliser
+  float* col_part;   // [Bz, Hkv * n_rsplit, Nv] column sums per layer, KV head and row run
   float* s_attn;     // [B, Nv]
   float* s_temp;     // [B, Nv]
   float* s_spa;      // [B, Nv]

@@ -19,10 +19,11 @@ namespace hippo {
 constexpr int kSaValuTile = 32;
 
 // Where pass 1 leaves the (max, sum) of query row r = i*G + g of KV head hk for token tile `tile`:
-// tile-major slabs of all B*H*L rows in (b, hk, r) order, so a block writes consecutive floats and
-// the merge reads consecutive rows.  row_lse uses the same (b, hk, r) order.
+// tile-major slabs of all Bz*H*L rows in (bz, hk, r) order, so a block writes consecutive floats and
+// the merge reads consecutive rows; bz = layer * B + b counts (layer, batch element) pairs when several
+// layers are swept in one launch.  row_lse uses the same (bz, hk, r) order.
 __device__ __forceinline__ long long sattn_part_at(const ScoreParams& p, int tile, int b, int hk, int r) {
-  return (long long)tile * ((long long)p.B * p.H * p.L) + ((long long)b * p.Hkv + hk) * ((long long)p.L * p.G) + r;
+  return (long long)tile * ((long long)p.Bz * p.H * p.L) + ((long long)b * p.Hkv + hk) * ((long long)p.L * p.G) + r;
 }
 
 template <typename T, int D, int PASS>
@@ -35,13 +36,15 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
   __shared__ float col_s[8][TT];
 
   const int tid = threadIdx.x, tok = tid & 31, rg = tid >> 5;
-  const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int tile = blockIdx.x, hk = blockIdx.y, bz = blockIdx.z;
+  const int b = bz % p.B, layer = bz / p.B;          // several layers' sweeps share a launch
   const int n0 = tile * TT;
   const int Rs = p.L * p.G;
   const float scale_log2 = rsqrtf((float)D) * kLog2e;
 
-  const T* kbase = (const T*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
+  const T* kbase = (const T*)p.k_layers[layer] + (long long)b * p.sb + (long long)hk * p.sh +
                    (long long)p.vis_off * p.sn;
+  const T* qlayer = (const T*)p.q_layers[layer];
   for (int e = tid; e < TT * VPR; e += 256) {
     const int row = e / VPR, vec = e % VPR, n = n0 + row;
     float kf[Elem<T>::kPerVec];
@@ -65,14 +68,14 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
       float val = 0.f;
       if (r < Rs) {
         const int i = r / p.G, gq = r % p.G;
-        val = Elem<T>::load((const T*)p.q_txt + (((long long)b * p.L + i) * p.H + hk * p.G + gq) * D + c);
+        val = Elem<T>::load(qlayer + (((long long)b * p.L + i) * p.H + hk * p.G + gq) * D + c);
       }
       Qs[rr][c] = val;
     }
     if (PASS == 2 && tid < RC) {
       const int r = r0 + tid;
       float v = INFINITY;   // padding rows contribute exp2(-inf) = 0
-      if (r < Rs) v = p.row_lse[((long long)b * p.Hkv + hk) * Rs + r];
+      if (r < Rs) v = p.row_lse[((long long)bz * p.Hkv + hk) * Rs + r];
       lse_s[tid] = v;
     }
     __syncthreads();
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
         if (tok == 0 && r < Rs) {
-          const long long at = sattn_part_at(p, tile, b, hk, r);
+          const long long at = sattn_part_at(p, tile, bz, hk, r);
           p.row_m[at] = mx;
           p.row_l[at] = ps;
         }
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
       float t = 0.f;
 #pragma unroll
       for (int w = 0; w < 8; ++w) t += col_s[w][tid];
-      p.col_part[((long long)b * p.Hkv + hk) * p.Nv + n0 + tid] = t;
+      p.col_part[((long long)bz * p.Hkv + hk) * p.Nv + n0 + tid] = t;
     }
   }
 }
@@ -136,7 +139,8 @@ struct SattnSmem {
 
 template <int D, int PASS>
 __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<D, PASS>& sm, const int tile,
-                                                const int vhk, const int b) {
+                                                const int vhk, const int bz) {
+  const int b = bz % p.B, layer = bz / p.B;          // several layers' sweeps share a launch
   constexpr int NW = kSaWaves, NT = NW * 64;
   constexpr int TPW = kSaMfmaTile / NW;   // tokens per wave
   constexpr int TBW = TPW / 16;           // 16-token blocks per wave
@@ -161,7 +165,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
   const int row_begin = rs * rows_per_split;
   const int row_end = min(Rs, row_begin + rows_per_split);
 
-  const uint16_t* kbase = (const uint16_t*)p.k_cache + (long long)b * p.sb + (long long)hk * p.sh +
+  const uint16_t* kbase = (const uint16_t*)p.k_layers[layer] + (long long)b * p.sb + (long long)hk * p.sh +
                           (long long)p.vis_off * p.sn;
   // this wave's keys as A operands: token tb*16 + j, head-dim elements (g*KS + ks)*8 .. +8
   bf16x8 kop[TBW][KS];
@@ -195,7 +199,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
   // Row r = i*G + g of the KV head lives at ((b*L + i)*H + hk*G + g)*D.  The (i, g) of the rows this
   // thread stages are carried from chunk to chunk (a chunk advances every row by RCH), so the
   // division by G happens once, not per chunk.
-  const uint16_t* qbase = (const uint16_t*)p.q_txt + ((long long)b * p.L * p.H + hk * p.G) * D;
+  const uint16_t* qbase = (const uint16_t*)p.q_layers[layer] + ((long long)b * p.L * p.H + hk * p.G) * D;
   int qi[QPT], qg[QPT];
   const int step_i = RCH / p.G, step_g = RCH % p.G;
 #pragma unroll
@@ -220,7 +224,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
     if (PASS == 2 && tid < RCH) {
       const int r = r0 + tid;
       lse_reg = INFINITY;                     // padding rows contribute exp2(-inf) = 0
-      if (r < Rs) lse_reg = p.row_lse[((long long)b * p.Hkv + hk) * Rs + r];
+      if (r < Rs) lse_reg = p.row_lse[((long long)bz * p.Hkv + hk) * Rs + r];
     }
   };
   fetch_chunk(row_begin);
@@ -298,7 +302,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 #pragma unroll
         for (int w = 0; w < NW; ++w)
           ll += (wm_s[w][rr] == -INFINITY) ? 0.f : wl_s[w][rr] * fast_exp2(wm_s[w][rr] - mm);
-        const long long at = sattn_part_at(p, tile, b, hk, base + rr);   // consecutive rows: coalesced
+        const long long at = sattn_part_at(p, tile, bz, hk, base + rr);  // consecutive rows: coalesced
         p.row_m[at] = mm;
         p.row_l[at] = ll;
       }
@@ -314,7 +318,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
         if (j == 0 && tok_ok[tb][e])
-          p.col_part[((long long)b * p.Hkv * p.n_rsplit + vhk) * p.Nv + n0 + tb * 16 + 4 * g + e] = v;
+          p.col_part[((long long)bz * p.Hkv * p.n_rsplit + vhk) * p.Nv + n0 + tb * 16 + 4 * g + e] = v;
       }
   }
 }
@@ -330,7 +334,7 @@ __global__ __launch_bounds__(kSaWaves * 64) void sattn_mfma(ScoreParams p) {
 // slices of a row then merge through LDS.  Consecutive threads read consecutive rows of a tile's slab.
 __global__ __launch_bounds__(256) void sattn_row_lse(ScoreParams p) {
   __shared__ float sm[8][32], sl[8][32];
-  const long long rows = (long long)p.B * p.H * p.L;
+  const long long rows = (long long)p.Bz * p.H * p.L;
   const int rl = threadIdx.x & 31, slice = threadIdx.x >> 5;
   const long long row = (long long)blockIdx.x * 32 + rl;
   float mm = -INFINITY, ll = 0.f;
@@ -374,7 +378,10 @@ __global__ __launch_bounds__(256) void sattn_finalize(ScoreParams p) {
   if (e >= (long long)p.B * p.Nv) return;
   const int b = (int)(e / p.Nv), jj = (int)(e % p.Nv);
   float a = 0.f;
-  for (int hk = 0; hk < p.Hkv * p.n_rsplit; ++hk) a += p.col_part[((long long)b * p.Hkv * p.n_rsplit + hk) * p.Nv + jj];
+  const int nvh = p.Hkv * p.n_rsplit;
+  for (int layer = 0; layer < p.n_layers; ++layer)
+    for (int hk = 0; hk < nvh; ++hk)
+      a += p.col_part[(((long long)layer * p.B + b) * nvh + hk) * p.Nv + jj];
   a /= (float)p.H * (float)p.L;
   if (p.attn_mass_inout != nullptr) {
     a += p.attn_mass_inout[e];
@@ -874,7 +881,10 @@ __global__ __launch_bounds__(256) void fuse_scores(ScoreParams p) {
       const long long e = base + i;
       const int jj = f * p.P + i;
       float a = 0.f;
-      for (int hk = 0; hk < p.Hkv * p.n_rsplit; ++hk) a += p.col_part[((long long)b * p.Hkv * p.n_rsplit + hk) * p.Nv + jj];
+      const int nvh = p.Hkv * p.n_rsplit;
+      for (int layer = 0; layer < p.n_layers; ++layer)
+        for (int hk = 0; hk < nvh; ++hk)
+          a += p.col_part[(((long long)layer * p.B + b) * nvh + hk) * p.Nv + jj];
       a /= (float)p.H * (float)p.L;
       if (p.attn_mass_inout != nullptr) {
         a += p.attn_mass_inout[e];
@@ -934,7 +944,9 @@ __global__ __launch_bounds__(256) void fuse_scores_reg(ScoreParams p) {
     x[0][u] = x[1][u] = x[2][u] = 0.f;
     if (ok && on[0]) {
       float a = 0.f;
-      for (int hk = 0; hk < nvh; ++hk) a += p.col_part[((long long)b * nvh + hk) * p.Nv + (long long)f * p.P + i];
+      for (int layer = 0; layer < p.n_layers; ++layer)
+        for (int hk = 0; hk < nvh; ++hk)
+          a += p.col_part[(((long long)layer * p.B + b) * nvh + hk) * p.Nv + (long long)f * p.P + i];
       a /= (float)p.H * (float)p.L;
       if (p.attn_mass_inout != nullptr) {
         a += p.attn_mass_inout[base + i];
@@ -1010,9 +1022,9 @@ int score_row_splits(int dtype, long long blocks_unsplit, int rows_per_kv_head) 
 
 template <typename T, int D>
 static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
-  dim3 grid(p.n_tile, p.Hkv, p.B);
+  dim3 grid(p.n_tile, p.Hkv, p.Bz);
   hipLaunchKernelGGL((sattn_valu<T, D, 1>), grid, dim3(256), 0, st, p);
-  const long long rows = (long long)p.B * p.H * p.L;
+  const long long rows = (long long)p.Bz * p.H * p.L;
   hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, p);
   hipLaunchKernelGGL((sattn_valu<T, D, 2>), grid, dim3(256), 0, st, p);
   return hipGetLastError();
@@ -1020,16 +1032,16 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
 
 template <int D>
 static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st, bool with_emb) {
-  dim3 grid(p.n_tile, p.Hkv * p.n_rsplit, p.B);
+  dim3 grid(p.n_tile, p.Hkv * p.n_rsplit, p.Bz);
   if (with_emb) {
-    const long long n_sattn = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.B;
+    const long long n_sattn = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.Bz;
     const long long n_crops = (long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B;
     hipLaunchKernelGGL((sattn_pass1_with_emb<D>), dim3((unsigned)(n_sattn + (n_crops + 1) / 2)),
                        dim3(kSaWaves * 64), 0, st, p, (int)n_sattn);
   } else {
     hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(kSaWaves * 64), 0, st, p);
   }
-  const long long rows = (long long)p.B * p.H * p.L;
+  const long long rows = (long long)p.Bz * p.H * p.L;
   hipLaunchKernelGGL(sattn_row_lse, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, p);
   hipLaunchKernelGGL((sattn_mfma<D, 2>), grid, dim3(kSaWaves * 64), 0, st, p);
   return hipGetLastError();
@@ -1040,7 +1052,7 @@ hipError_t launch_score(const ScoreParams& p, hipStream_t st) {
   const bool accumulate_only = (p.flags & HIPPO_SCORE_ACCUMULATE_ONLY) != 0;
   // bf16 with the paper's small crops: the embedding terms ride in the launch of s_attn's pass 1
   const bool want_emb = (p.flags & (HIPPO_SCORE_TEMP | HIPPO_SCORE_SPA)) != 0;
-  const long long fused_blocks = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.B +
+  const long long fused_blocks = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.Bz +
       ((long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B + 1) / 2;
   const bool emb_rides = want_emb && !accumulate_only && (p.flags & HIPPO_SCORE_ATTN) &&
                          p.dtype == HIPPO_DTYPE_BF16 && p.ch * p.cw <= 32 && fused_blocks < (1ll << 31);

@@ -181,3 +181,52 @@ def test_prune_pipeline(hippo, name):
     torch.cuda.synchronize()
     ro, _ = oracle.attention(x["q_new"][:, :1], host(kpn), host(vpn), kp.shape[2])
     assert_close(host(out), ro, dt, name + " draft attention")
+
+
+# ---------------------------------------------------------------------------------------------
+# Eq. 2's sum over layers inside one call
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,n_layers", [("tiny", 3), ("draft", 4), ("draft", 1)])
+def test_score_layers_in_one_call(hippo, name, n_layers):
+    cfg = si.CONFIGS[name]
+    dt, n = cfg.dtype, cfg.ctx_len
+    xs = [si.make_inputs(cfg, 10 + l) for l in range(n_layers)]
+    vid = hippo.video_desc(cfg.n_frames, cfg.grid_h, cfg.grid_w, cfg.n_prefix)
+    qs = [dev(x["q_txt"], dt) for x in xs]
+    ks = [dev(x["k"][:, :, :n], dt) for x in xs]
+    emb_layer = n_layers - 1
+    scores, comps = hippo.hippo_score_tokens_layers(qs, ks, vid, emb_layer=emb_layer, want_components=True)
+    torch.cuda.synchronize()
+    sa = sum(oracle.s_attn(x["q_txt"], x["k"][:, :, :n], cfg.n_prefix, cfg.n_visual) for x in xs)
+    emb = oracle.keys_as_embedding(xs[emb_layer]["k"][:, :, :n], cfg.n_prefix, cfg.n_visual)
+    st = oracle.s_temp(emb, cfg.n_frames)
+    ss = oracle.s_spa(emb, cfg.n_frames, cfg.grid_h, cfg.grid_w)
+    assert_close(host(comps[0]), sa, dt, "layer-summed s_attn")
+    assert_close(host(comps[1]), st, dt, "s_temp")
+    ref = oracle.fuse(sa, st, ss, cfg.n_frames)
+    if dt == "fp32":
+        # Eq. 7 divides by the per-frame deviation: a raw term held to 1e-5 relative moves its z-score by
+        # up to 1e-5 (|x| + |mean|) / sigma (plus the z-score's own 1e-5 through sigma), which on these
+        # inputs is a few times 1e-5 of an O(1) value -- bound each element by that propagated error
+        P = cfg.grid_h * cfg.grid_w
+        bound = np.zeros_like(ref)
+        for t in (sa, st, ss):
+            tf = t.reshape(cfg.batch, cfg.n_frames, P)
+            mu, sg = tf.mean(-1, keepdims=True), tf.std(-1, keepdims=True)
+            amp = np.where(sg > 0, (np.abs(tf) + np.abs(mu)) / np.where(sg > 0, sg, 1) + np.abs((tf - mu) / np.where(sg > 0, sg, 1)), 0)
+            bound += 1e-5 * amp.reshape(ref.shape)
+        assert np.all(np.abs(host(scores) - ref) <= bound + 1e-5 * np.abs(ref)), "fused over %d layers" % n_layers
+    else:
+        assert_close(host(scores), ref, dt, "fused over %d layers" % n_layers)
+    # the same through per-layer calls with the accumulate flag (what the batched call replaces)
+    mass = torch.zeros((cfg.batch, cfg.n_visual), dtype=torch.float32, device="cuda")
+    for l in range(n_layers - 1):
+        hippo.hippo_score_tokens(qs[l], ks[l], vid, flags=hippo.SCORE_ACCUMULATE_ONLY, attn_mass_inout=mass)
+    seq = hippo.hippo_score_tokens(qs[-1], ks[-1], vid, attn_mass_inout=mass)
+    torch.cuda.synchronize()
+    # two fp32 paths to the same number: twice the propagated bound apart at most
+    if dt == "fp32":
+        assert np.all(np.abs(host(seq) - host(scores)) <= 2 * bound + 2e-5 * np.abs(ref)), "batched vs accumulated"
+    else:
+        assert_close(host(seq), host(scores).astype(np.float64), dt, "batched vs accumulated")
