@@ -216,3 +216,27 @@ def test_attention_paged_argument_errors(lib):
     assert call(splits=1) == h.ERR_BAD_SHAPE
     assert lib.hippo_verify_attention_paged(FAKE, 6, FAKE, FAKE, FAKE, None, 10, 0.0, 0, FAKE, None, FAKE, 1 << 20,
                                             None) == h.ERR_NULL_ARG
+
+
+def test_score_layers_argument_errors(lib):
+    kv, vid = _kv(), h.video_desc(64, 16, 16, 128)
+    need1 = lib.hippo_score_layers_workspace_bytes(C.byref(kv), C.byref(vid), 128, 1)
+    need4 = lib.hippo_score_layers_workspace_bytes(C.byref(kv), C.byref(vid), 128, 4)
+    assert need1 == h.workspace_bytes(h.CALL_SCORE_TOKENS, kv, vid, 128, 16646) and need4 > 2 * need1
+    assert lib.hippo_score_layers_workspace_bytes(C.byref(kv), C.byref(vid), 128, 65) == 0
+
+    def call(n=4, qs=None, ks=None, emb_layer=0, ws_bytes=need4, scores=FAKE):
+        qa = (C.c_void_p * 4)(*(qs or [FAKE] * 4))
+        ka = (C.c_void_p * 4)(*(ks or [FAKE] * 4))
+        return lib.hippo_score_tokens_layers(n, C.cast(qa, C.c_void_p), 128, C.cast(ka, C.c_void_p), emb_layer,
+                                             C.byref(kv), 16646, C.byref(vid), None, 0, 0, h.SCORE_ALL, None, scores,
+                                             None, FAKE, ws_bytes, None)
+    assert call(n=0) == h.ERR_BAD_SHAPE
+    assert call(n=65) == h.ERR_BAD_SHAPE
+    assert call(emb_layer=4) == h.ERR_BAD_SHAPE
+    assert call(qs=[FAKE, None, FAKE, FAKE]) == h.ERR_NULL_ARG
+    assert call(ks=[FAKE, FAKE, FAKE + 8, FAKE]) == h.ERR_BAD_ALIGN
+    assert call(scores=None) == h.ERR_NULL_ARG
+    assert call(ws_bytes=need1) == h.ERR_WORKSPACE_TOO_SMALL
+    assert lib.hippo_score_tokens_layers(1, None, 128, None, 0, C.byref(kv), 16646, C.byref(vid), None, 0, 0, 7, None,
+                                         FAKE, None, FAKE, need1, None) == h.ERR_NULL_ARG
