@@ -4,6 +4,13 @@
  * and the two attention calls that video parallel speculative decoding overlaps (draft decode over
  * the pruned cache, target verification of gamma+1 tokens over the full cache).
  *
+ * The hot path proper:   hippo_score_tokens, hippo_select_gather_kv, hippo_draft_attention,
+ *                        hippo_verify_attention (+ hippo_workspace_bytes, hippo_status_string).
+ * Built around it:       hippo_score_tokens_layers (Eq. 2's layer sum in one call),
+ *                        hippo_*_attention_append and hippo_*_attention_paged (cache-format variants),
+ *                        hippo_spec_verify (the speculative-sampling verdict of Eq. 1),
+ *                        hippo_vpsd_* (host-side control of the parallel decoding rounds).
+ *
  * Conventions common to every entry point
  *  - All data pointers are DEVICE pointers owned and allocated by the caller.  The library never
  *    allocates or frees device memory and never synchronises: it validates its arguments on the
