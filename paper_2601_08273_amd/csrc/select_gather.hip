@@ -86,13 +86,13 @@ __device__ __forceinline__ void walk_histogram(const unsigned* h, int nb, int la
   }
 }
 
-// One block per sequence.  NC > 0: every thread keeps its keys (index c*1024 + tid, c < NC) in
+// One block per sequence.  NC > 0: every thread keeps NC consecutive keys (indices tid*NC ..) in
 // registers, so the scores are read from memory once and every loop over them is unrolled to the
-// sequence's size class; NC = 0: any length, each pass re-reads the scores.
+// sequence's size class; NC = 0: any length, keys strided over the threads, each pass re-reads them.
 // Radix select with digits of 12, 12 and 8 bits: the wide first digit (sign, exponent, 3 mantissa
 // bits) spreads scores of similar magnitude over many LDS bins, which keeps same-address atomic
-// traffic low.  The compaction is index-ordered: per-(chunk, wave) counts, one scan, then each key
-// computes its slot from the scan and its rank inside the wave.
+// traffic low.  The compaction is index-ordered: per-thread counts and one scan when the keys are
+// cached, per-(chunk, wave) ballots with running totals otherwise.
 template <int NC>
 __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   constexpr bool CACHED = NC > 0;
@@ -110,16 +110,28 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
 
   TOPK_TP_DECL
   TOPK_TP(0)
+  // CACHED: thread t owns the NC consecutive scores t*NC .. t*NC+NC-1 (index order = thread order,
+  // which makes the compaction a per-thread count plus one scan); 16-byte loads where the row allows
   unsigned keys[CACHED ? NC : 1];
+  const int first = tid * NC;                // CACHED only
   if (CACHED) {
+    const bool vec_ok = (NC % 4 == 0) && ((((long long)b * p.Nv) & 3) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(p.scores) & 15u) == 0);
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int i = c * kSelThreads + tid;
-      keys[c] = (c < n_chunks && i < p.Nv) ? score_key(sc[i]) : 0u;
+    for (int c0 = 0; c0 < NC; c0 += 4) {
+      if (NC % 4 == 0 && vec_ok && first + c0 + 3 < p.Nv) {
+        const f32x4 v = *(const f32x4*)(sc + first + c0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) keys[c0 + e] = score_key(v[e]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (c0 + e < NC) keys[c0 + e] = (first + c0 + e < p.Nv) ? score_key(sc[first + c0 + e]) : 0u;
+      }
     }
   }
-  auto key_at = [&](int c) -> unsigned {     // key of chunk c for this thread (index must be < Nv)
-    return CACHED ? keys[c] : score_key(sc[c * kSelThreads + tid]);
+  auto key_at = [&](int c) -> unsigned {     // NC = 0: key of chunk c for this thread (index must be < Nv)
+    return score_key(sc[c * kSelThreads + tid]);
   };
 
   TOPK_TP(1)
@@ -137,7 +149,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     if (CACHED) {
 #pragma unroll
       for (int c = 0; c < NC; ++c)
-        if (c < n_chunks && c * kSelThreads + tid < p.Nv && (keys[c] & masks[pass]) == prefix)
+        if (first + c < p.Nv && (keys[c] & masks[pass]) == prefix)
           atomicAdd(&h[hist_slot((keys[c] >> shifts[pass]) & dmask[pass])], 1u);
     } else {
       for (int c = 0; c < n_chunks; ++c)
@@ -195,11 +207,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   const unsigned need_eq = need;    // how many keys equal to it are kept (lowest indices first)
 
   // ---- compaction in index order ----
-  // counts per (chunk, wave) in chunk-major order reuse the histogram storage: [2][n_chunks*16]
-  unsigned* cnt_gt = hist;
-  unsigned* cnt_eq = hist + kKeysPerThread * kSelWaves;     // 2 x 640 entries, well inside hist
   __syncthreads();
-  auto flags = [&](int c, bool& gt, bool& eq) {
+  auto flags = [&](int c, bool& gt, bool& eq) {        // NC = 0 path
     gt = eq = false;
     if (c * kSelThreads + tid < p.Nv) {
       const unsigned key = key_at(c);
@@ -208,58 +217,41 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     }
   };
   if (CACHED) {
+    // per-thread counts of keys above / equal to the threshold, packed (both fit 16 bits: a block
+    // caches at most 40960 keys), one block-wide exclusive scan, then every thread writes its own
+    // survivors in order
+    unsigned cg = 0, ce = 0;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      if (c < n_chunks) {
-        bool gt, eq;
-        flags(c, gt, eq);
-        const unsigned long long bg = __ballot(gt), be = __ballot(eq);
-        if (lane == 0) { cnt_gt[c * kSelWaves + wave] = __popcll(bg); cnt_eq[c * kSelWaves + wave] = __popcll(be); }
-      }
+      const bool ok = first + c < p.Nv;
+      cg += (ok && keys[c] > thr) ? 1u : 0u;
+      ce += (ok && keys[c] == thr) ? 1u : 0u;
     }
+    const unsigned mine = (cg << 16) | ce;
+    unsigned incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned n = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += n;
+    }
+    if (lane == 63) wave_tot[0][wave] = incl;
     __syncthreads();
     TOPK_TP(5)
-    // exclusive scan of both count arrays in (chunk, wave) order, by one wave: n_chunks * waves
-    // <= 640 entries, up to 10 consecutive ones per lane, read in one batch
-    if (wave == 0) {
-      const int n_ent = n_chunks * kSelWaves;
-      constexpr int EPL = (kKeysPerThread * kSelWaves + 63) / 64;       // entries per lane
-      unsigned sg = 0, se = 0;
+    unsigned tot[kSelWaves];
 #pragma unroll
-      for (int q = 0; q < EPL; ++q) {
-        const int e = lane * EPL + q;
-        sg += e < n_ent ? cnt_gt[e] : 0u;
-        se += e < n_ent ? cnt_eq[e] : 0u;
-      }
-      unsigned ig = sg, ie = se;
+    for (int w = 0; w < kSelWaves; ++w) tot[w] = wave_tot[0][w];
+    unsigned before = incl - mine;
 #pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const unsigned ng = __shfl_up(ig, o, 64), ne = __shfl_up(ie, o, 64);
-        if (lane >= o) { ig += ng; ie += ne; }
-      }
-      unsigned rg = ig - sg, re = ie - se;
-#pragma unroll
-      for (int q = 0; q < EPL; ++q) {               // a lane rewrites only its own entries
-        const int e = lane * EPL + q;
-        if (e < n_ent) {
-          const unsigned g0 = cnt_gt[e], e0 = cnt_eq[e];
-          cnt_gt[e] = rg; cnt_eq[e] = re;
-          rg += g0; re += e0;
-        }
-      }
-    }
-    __syncthreads();
+    for (int w = 0; w < kSelWaves; ++w) before += (w < wave) ? tot[w] : 0u;
+    unsigned gt_before = before >> 16, eq_before = before & 0xffffu;
     TOPK_TP(6)
-    const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      if (c < n_chunks) {
-        bool gt, eq;
-        flags(c, gt, eq);
-        const unsigned long long bg = __ballot(gt), be = __ballot(eq);
-        const unsigned gt_before = cnt_gt[c * kSelWaves + wave] + __popcll(bg & below);
-        const unsigned eq_before = cnt_eq[c * kSelWaves + wave] + __popcll(be & below);
-        if (gt || (eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = c * kSelThreads + tid;
+      if (first + c < p.Nv) {
+        const bool gt = keys[c] > thr, eq = keys[c] == thr;
+        if (gt || (eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = first + c;
+        gt_before += gt ? 1u : 0u;
+        eq_before += eq ? 1u : 0u;
       }
     }
   } else {
