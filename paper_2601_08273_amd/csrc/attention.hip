@@ -596,42 +596,60 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
                        : (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  // this thread's first slice statistics ride in the same trip (S <= 256 is the usual case)
-  const float m0 = tid < p.S ? p.part_m[(slot0 + tid) * p.R + r] : -INFINITY;
-  const float l0 = tid < p.S ? p.part_l[(slot0 + tid) * p.R + r] : 0.f;
-  float mloc = m0;
-  for (int s = tid + 256; s < p.S; s += 256) mloc = fmaxf(mloc, p.part_m[(slot0 + s) * p.R + r]);
-  mloc = wave_max(mloc);
-  if ((tid & 63) == 0) red[tid >> 6] = mloc;
-  __syncthreads();
-  const float mstar = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  float dloc = 0.f;
-  if (tid < p.S) {
-    const float w = (m0 == -INFINITY) ? 0.f : fast_exp2(m0 - mstar);
-    w_s[tid] = w;
-    dloc = w * l0;
-  }
-  for (int s = tid + 256; s < p.S; s += 256) {
-    const float ms = p.part_m[(slot0 + s) * p.R + r];
-    const float w = (ms == -INFINITY) ? 0.f : fast_exp2(ms - mstar);
-    w_s[s] = w;
-    dloc = fmaf(w, p.part_l[(slot0 + s) * p.R + r], dloc);
-  }
-  dloc = wave_sum(dloc);
-  if ((tid & 63) == 0) red[4 + (tid >> 6)] = dloc;
-  __syncthreads();
-  const float den = red[4] + red[5] + red[6] + red[7];
-
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float mstar, den;
+  if (p.S <= 64) {
+    // up to 64 slices: every wave holds all slice statistics (one per lane), so the reference
+    // maximum, the weights and the denominator need no LDS and no barrier; a weight reaches the
+    // thread that needs it through a lane shuffle
+    const int lane = tid & 63;
+    const float ms = lane < p.S ? p.part_m[(slot0 + lane) * p.R + r] : -INFINITY;
+    const float ls = lane < p.S ? p.part_l[(slot0 + lane) * p.R + r] : 0.f;
+    mstar = wave_max(ms);
+    const float w = (ms == -INFINITY) ? 0.f : fast_exp2(ms - mstar);
+    den = wave_sum(w * ls);
 #pragma unroll
-  for (int u = 0; u < PF; ++u) {
-    const int s = sg + u * NSG;
-    if (s < p.S) acc += pre[u] * w_s[s];
-  }
+    for (int u = 0; u < PF; ++u) {
+      const int sl = sg + u * NSG;                        // < 64 whenever it is < S
+      const float ws = __shfl(w, sl & 63, 64);
+      if (sl < p.S) acc += pre[u] * ws;
+    }
+  } else {
+    // this thread's first slice statistics ride in the same trip
+    const float m0 = tid < p.S ? p.part_m[(slot0 + tid) * p.R + r] : -INFINITY;
+    const float l0 = tid < p.S ? p.part_l[(slot0 + tid) * p.R + r] : 0.f;
+    float mloc = m0;
+    for (int s2 = tid + 256; s2 < p.S; s2 += 256) mloc = fmaxf(mloc, p.part_m[(slot0 + s2) * p.R + r]);
+    mloc = wave_max(mloc);
+    if ((tid & 63) == 0) red[tid >> 6] = mloc;
+    __syncthreads();
+    mstar = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float dloc = 0.f;
+    if (tid < p.S) {
+      const float w = (m0 == -INFINITY) ? 0.f : fast_exp2(m0 - mstar);
+      w_s[tid] = w;
+      dloc = w * l0;
+    }
+    for (int s2 = tid + 256; s2 < p.S; s2 += 256) {
+      const float ms = p.part_m[(slot0 + s2) * p.R + r];
+      const float w = (ms == -INFINITY) ? 0.f : fast_exp2(ms - mstar);
+      w_s[s2] = w;
+      dloc = fmaf(w, p.part_l[(slot0 + s2) * p.R + r], dloc);
+    }
+    dloc = wave_sum(dloc);
+    if ((tid & 63) == 0) red[4 + (tid >> 6)] = dloc;
+    __syncthreads();
+    den = red[4] + red[5] + red[6] + red[7];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int sl = sg + u * NSG;
+      if (sl < p.S) acc += pre[u] * w_s[sl];
+    }
 #pragma unroll 4
-  for (int s = sg + PF * NSG; s < p.S; s += NSG) {
-    const f32x4 o = *(const f32x4*)(p.part_o + ((slot0 + s) * p.R + r) * D + vec * 4);
-    acc += o * w_s[s];
+    for (int sl = sg + PF * NSG; sl < p.S; sl += NSG) {
+      const f32x4 o = *(const f32x4*)(p.part_o + ((slot0 + sl) * p.R + r) * D + vec * 4);
+      acc += o * w_s[sl];
+    }
   }
   acc_s[sg][vec] = acc;
   __syncthreads();
