@@ -533,8 +533,11 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   f32x4* xbuf = (f32x4*)ring;                              // [WAVES][DB][64 lanes]
   __syncthreads();   // (a) every wave is done reading the ring before anyone overwrites it
   HIPPO_TP(7)
+  // a wave finishes head-dim blocks tg, tg + TG, ...: those stay in its registers, only the blocks
+  // that other waves finish go through LDS
 #pragma unroll
-  for (int db = 0; db < DB; ++db) xbuf[(wave * DB + db) * 64 + lane] = acc[db];
+  for (int db = 0; db < DB; ++db)
+    if (db % TG != tg) xbuf[(wave * DB + db) * 64 + lane] = acc[db];
   __syncthreads();   // (b) accumulators and statistics of all waves visible
   {
     float mw[TG], mm = -INFINITY;
@@ -550,9 +553,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 #pragma unroll
     for (int dd = 0; dd < DB / TG; ++dd) {
       const int db = tg + TG * dd;
-      f32x4 o = xbuf[((0 * RB + rb) * DB + db) * 64 + lane] * f[0];
+      f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int w = 1; w < TG; ++w) o += xbuf[((w * RB + rb) * DB + db) * 64 + lane] * f[w];
+      for (int w = 0; w < TG; ++w) {
+        if (w == tg) o += acc[w + TG * dd] * f[w];                        // tg is wave-uniform
+        else o += xbuf[((w * RB + rb) * DB + db) * 64 + lane] * f[w];
+      }
       if (row < p.R) *(f32x4*)(p.part_o + (slot * p.R + row) * D + db * 16 + 4 * g) = o;
     }
     if (tg == 0 && g == 0 && row < p.R) {
