@@ -185,6 +185,64 @@ def attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, ctx_len: 
     return out, lse
 
 
+def _attention64(q: np.ndarray, k: np.ndarray, v: np.ndarray, ctx_len: int,
+                 scale: Optional[float]) -> Tuple[np.ndarray, np.ndarray]:
+    """The same definition as `attention` for float64 caches, as dense numpy operations:
+    per head, z = scale * q K^T, entries beyond ctx_len + i masked for row i, softmax, times V."""
+    B, q_len, H, d = q.shape
+    _, Hkv, N, _ = k.shape
+    assert N >= ctx_len + q_len and v.shape == k.shape and H % Hkv == 0
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    n = ctx_len + q_len
+    visible = np.arange(n)[None, :] <= ctx_len + np.arange(q_len)[:, None]
+    out = np.zeros((B, q_len, H, d), dtype=np.float64)
+    lse = np.zeros((B, H, q_len), dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            hk = h // (H // Hkv)
+            z = scale * (q[b, :, h, :] @ k[b, hk, :n, :].T)
+            z = np.where(visible, z, -np.inf)
+            zmax = z.max(axis=1, keepdims=True)
+            w = np.exp(z - zmax)
+            denom = w.sum(axis=1, keepdims=True)
+            out[b, :, h, :] = (w / denom) @ v[b, hk, :n, :]
+            lse[b, h, :] = (zmax + np.log(denom))[:, 0]
+    return out, lse
+
+
+def e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    """8-bit floating-point codes, 1 sign / 4 exponent / 3 mantissa bits, exponent bias 7, the
+    finite-only variant (OCP 8-bit floating point specification, E4M3: no infinities; exponent 15
+    with mantissa 7 is NaN; exponent 0 is subnormal) -> float64, written out from that definition.
+    A format the paper does not mention: it serves the fp8 cache variant of the attention calls."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c >> 7 == 1, -1.0, 1.0)
+    e = (c >> 3) & 15
+    m = (c & 7).astype(np.float64)
+    normal = (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64))
+    subnormal = (m / 8.0) * 2.0 ** -6
+    val = np.where(e == 0, subnormal, normal)
+    val = np.where((e == 15) & (m == 7), np.nan, val)
+    return sign * val
+
+
+def attention_fp8kv(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray, k_scale: np.ndarray,
+                    v_scale: np.ndarray, ctx_len: int, scale: Optional[float] = None
+                    ) -> Tuple[np.ndarray, np.ndarray]:
+    """The attention call over a cache stored as E4M3 codes with one fp32 multiplier per (batch
+    element, KV head): the cache entry is multiplier * decoded code, and the result is `attention`
+    (paper: Preliminaries, "Speculative Decoding") of those entries.  k_codes / v_codes
+    [B,Hkv,N,d] uint8, k_scale / v_scale [B,Hkv]."""
+    ks = np.asarray(k_scale, dtype=np.float64)[:, :, None, None]
+    vs = np.asarray(v_scale, dtype=np.float64)[:, :, None, None]
+    k = e4m3_decode(k_codes) * ks
+    v = e4m3_decode(v_codes) * vs
+    # every product of a code value (4 significant bits) and an fp32 multiplier is exact in float64;
+    # `attention` takes float32 caches, so feed it through the float64 entry below
+    return _attention64(np.asarray(q, dtype=np.float64), k, v, ctx_len, scale)
+
+
 def spec_verify(p_logits: np.ndarray, q_logits: Optional[np.ndarray], tokens: np.ndarray,
                 u_accept: np.ndarray, u_sample: np.ndarray, temperature: float
                 ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:

@@ -221,3 +221,17 @@ def make_logits(n_batch: int, gamma: int, vocab: int, seed: int, closeness: floa
     np.put_along_axis(pl, hot, pl.max() + rng.random((n_batch, gamma + 1, 4)).astype(np.float32) * 4.0, axis=-1)
     ql = pl[:, :gamma] + closeness * rng.standard_normal((n_batch, gamma, vocab)).astype(np.float32)
     return pl, ql, rng
+
+
+def quantize_e4m3(x: np.ndarray):
+    """[B,Hkv,N,d] float array -> (uint8 E4M3 codes of the same shape, fp32 multipliers [B,Hkv]) with
+    multiplier = max|x| / 448 per (batch element, KV head) and codes = x / multiplier rounded to the
+    nearest representable value (ties to even) by the tensor library's own conversion.  Input
+    formatting only, like the bf16 rounding above."""
+    import torch
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    amax = np.abs(x).max(axis=(2, 3))
+    mult = np.where(amax > 0, amax / 448.0, 1.0).astype(np.float32)
+    y = torch.from_numpy(x / mult[:, :, None, None]).clamp_(-448.0, 448.0)
+    codes = y.to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+    return codes, mult
