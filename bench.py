@@ -185,6 +185,20 @@ def main():
             h.hippo_verify_attention_paged(qd[l], k_pool[l], v_pool[l], table_d, n_ctx, num_splits=args.num_splits,
                                            out=out_ver, workspace=ws_ver)
 
+    # fp8 cache: the same rows as E4M3 codes with one multiplier per (batch element, KV head)
+    have_fp8 = dt == "bf16"
+    if have_fp8:
+        def to_codes(x):
+            mult = (x.float().abs().amax(dim=(2, 3)) / 448.0).clamp_min(1e-30)
+            codes = (x.float() / mult[:, :, None, None]).clamp_(-448.0, 448.0).to(torch.float8_e4m3fn)
+            return codes, mult.contiguous()
+        k8, v8 = [to_codes(kd[l]) for l in range(L)], [to_codes(vd[l]) for l in range(L)]
+
+    def verify_fp8_all():
+        for l in range(L):
+            h.hippo_verify_attention_fp8kv(qd[l], k8[l][0], v8[l][0], k8[l][1], v8[l][1], n_ctx,
+                                           num_splits=args.num_splits, out=out_ver, workspace=ws_ver)
+
     # Eq. 2 summed over several layers: one call that sweeps them in shared launches, versus one
     # accumulate call per layer
     NLS = min(4, L)
@@ -249,6 +263,7 @@ def main():
     run_verify_append = capture(verify_append_all)
     run_copy_verify = capture(copy_then_verify_all)
     run_verify_paged = capture(verify_paged_all)
+    run_verify_fp8 = capture(verify_fp8_all) if have_fp8 else None
     run_layers_one = capture(score_layers_one_call)
     run_layers_acc = capture(score_layers_accumulate)
     run_sd_sampling = capture(spec_sampling)
@@ -303,6 +318,7 @@ def main():
     t_verify_append = alone(run_verify_append) / L
     t_copy_verify = alone(run_copy_verify) / L
     t_verify_paged = alone(run_verify_paged) / L
+    t_verify_fp8 = alone(run_verify_fp8) / L if have_fp8 else None
     t_layers_one = alone(run_layers_one)
     t_layers_acc = alone(run_layers_acc)
     t_sd_sampling = alone(run_sd_sampling) / SD_REPS
@@ -352,6 +368,7 @@ def main():
                "alone:verify_with_fused_append_per_layer": round(t_verify_append * 1e6, 3),
                "alone:copy_new_rows_then_verify_per_layer": round(t_copy_verify * 1e6, 3),
                "alone:verify_paged(16-token pages)_per_layer": round(t_verify_paged * 1e6, 3),
+               "alone:verify_fp8_cache_per_layer": round(t_verify_fp8 * 1e6, 3) if have_fp8 else None,
                "alone:score_%d_layers(one call)" % NLS: round(t_layers_one * 1e6, 2),
                "alone:score_%d_layers(accumulate calls)" % NLS: round(t_layers_acc * 1e6, 2),
                "alone:spec_verify(sampling, V=%d)" % V: round(t_sd_sampling * 1e6, 2),

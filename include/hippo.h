@@ -7,7 +7,8 @@
  * The hot path proper:   hippo_score_tokens, hippo_select_gather_kv, hippo_draft_attention,
  *                        hippo_verify_attention (+ hippo_workspace_bytes, hippo_status_string).
  * Built around it:       hippo_score_tokens_layers (Eq. 2's layer sum in one call),
- *                        hippo_*_attention_append and hippo_*_attention_paged (cache-format variants),
+ *                        hippo_*_attention_append, hippo_*_attention_paged and
+ *                        hippo_*_attention_fp8kv (cache-format variants),
  *                        hippo_spec_verify (the speculative-sampling verdict of Eq. 1),
  *                        hippo_vpsd_* (host-side control of the parallel decoding rounds).
  *
@@ -226,6 +227,30 @@ int hippo_draft_attention_append(const void* q, int32_t q_len, const void* k_new
                                  int32_t ctx_len, float softmax_scale, int32_t num_splits,
                                  void* out, float* lse_out,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same two attention calls over a cache stored in 8-bit floating point (a cache-format variant
+ * the paper does not discuss: it halves the bytes these bandwidth-bound calls stream).  k_codes /
+ * v_codes hold E4M3 codes (1 sign, 4 exponent, 3 mantissa bits, bias 7, finite-only: no infinities,
+ * 0x7f / 0xff are NaN), one byte per element, laid out as kv describes with strides counted in
+ * elements = bytes (multiples of 16).  k_scale / v_scale are DEVICE arrays [B, H_kv] of fp32
+ * multipliers, all > 0: the cache entry is multiplier * decoded code.  kv->dtype must be
+ * HIPPO_DTYPE_BF16: it is the type of q and out.  The result is that of hippo_verify_attention /
+ * hippo_draft_attention on the dequantised cache, computed with the same arithmetic as the bf16 path
+ * (codes convert to bf16 exactly; the K multiplier joins the softmax scale, the V multiplier the
+ * output).  Workspace: hippo_workspace_bytes with the same kv.  Caches are read only.
+ * Errors: as hippo_verify_attention, plus NULL_ARG for the multipliers, BAD_DTYPE unless bf16.
+ */
+int hippo_verify_attention_fp8kv(const void* q, int32_t q_len, const void* k_codes, const void* v_codes,
+                                 const float* k_scale, const float* v_scale, const hippo_kv_desc* kv,
+                                 int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                                 void* out, float* lse_out,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+int hippo_draft_attention_fp8kv(const void* q, int32_t q_len, const void* k_codes, const void* v_codes,
+                                const float* k_scale, const float* v_scale, const hippo_kv_desc* kv,
+                                int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                                void* out, float* lse_out,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The same two attention calls over a PAGED cache (a cache-format variant for serving stacks that

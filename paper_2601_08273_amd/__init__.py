@@ -23,6 +23,7 @@ EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
            "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention",
            "hippo_verify_attention_append", "hippo_draft_attention_append",
            "hippo_verify_attention_paged", "hippo_draft_attention_paged",
+           "hippo_verify_attention_fp8kv", "hippo_draft_attention_fp8kv",
            "hippo_spec_verify_workspace_bytes", "hippo_spec_verify", "hippo_vpsd_prefill_buffer",
            "hippo_vpsd_init", "hippo_vpsd_plan", "hippo_vpsd_commit", "hippo_vpsd_simulate")
 VPSD_CONSERVATIVE, VPSD_OPTIMISTIC = 0, 1
@@ -103,7 +104,8 @@ def load():
     for fn in (lib.hippo_verify_attention_paged, lib.hippo_draft_attention_paged):
         fn.argtypes = [vp, i32, vp, vp, vp, C.POINTER(PagedKvDesc), i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
-    for fn in (lib.hippo_verify_attention_append, lib.hippo_draft_attention_append):
+    for fn in (lib.hippo_verify_attention_append, lib.hippo_draft_attention_append,
+               lib.hippo_verify_attention_fp8kv, lib.hippo_draft_attention_fp8kv):
         fn.argtypes = [vp, i32, vp, vp, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
     f64 = C.c_double
@@ -322,6 +324,45 @@ def hippo_draft_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: floa
                           want_lse: bool = False, out=None, workspace=None, stream=None, k_new=None, v_new=None):
     return _attention("hippo_draft_attention", CALL_DRAFT_ATTENTION, q, k_cache, v_cache, ctx_len,
                       softmax_scale, num_splits, want_lse, out, workspace, stream, k_new, v_new)
+
+
+def _attention_fp8kv(fn_name, call, q, k_codes, v_codes, k_scale, v_scale, ctx_len, softmax_scale, num_splits,
+                     want_lse, out, workspace, stream):
+    torch = _torch()
+    lib = load()
+    assert q.is_contiguous() and q.dim() == 4 and q.dtype == torch.bfloat16
+    B, q_len, H, d = q.shape
+    assert k_codes.dim() == 4 and k_codes.stride(3) == 1 and k_codes.dtype in (torch.uint8, torch.float8_e4m3fn)
+    assert v_codes.shape == k_codes.shape and v_codes.stride() == k_codes.stride() and v_codes.dtype == k_codes.dtype
+    Hkv = k_codes.shape[1]
+    for t in (k_scale, v_scale):
+        assert t.shape == (B, Hkv) and t.is_contiguous() and t.dtype == torch.float32
+    kv = KvDesc(B, H, Hkv, d, DTYPE_BF16, k_codes.stride(0), k_codes.stride(1), k_codes.stride(2))
+    nbytes = workspace_bytes(call, kv, None, q_len, ctx_len + q_len, 0, num_splits)
+    ws = _workspace(nbytes, q.device, workspace)
+    if out is None:
+        out = torch.empty_like(q)
+    lse = torch.empty((B, H, q_len), dtype=torch.float32, device=q.device) if want_lse else None
+    st = getattr(lib, fn_name)(_ptr(q), q_len, _ptr(k_codes), _ptr(v_codes), _ptr(k_scale), _ptr(v_scale),
+                               C.byref(kv), ctx_len, float(softmax_scale or 0.0), num_splits, _ptr(out), _ptr(lse),
+                               _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, fn_name)
+    return (out, lse) if want_lse else out
+
+
+def hippo_verify_attention_fp8kv(q, k_codes, v_codes, k_scale, v_scale, ctx_len: int, softmax_scale: float = 0.0,
+                                 num_splits: int = 0, want_lse: bool = False, out=None, workspace=None,
+                                 stream=None):
+    """q [B,q_len,H,d] bf16; k_codes / v_codes [B,Hkv,N,d] E4M3 bytes; k_scale / v_scale [B,Hkv] fp32."""
+    return _attention_fp8kv("hippo_verify_attention_fp8kv", CALL_VERIFY_ATTENTION, q, k_codes, v_codes, k_scale,
+                            v_scale, ctx_len, softmax_scale, num_splits, want_lse, out, workspace, stream)
+
+
+def hippo_draft_attention_fp8kv(q, k_codes, v_codes, k_scale, v_scale, ctx_len: int, softmax_scale: float = 0.0,
+                                num_splits: int = 0, want_lse: bool = False, out=None, workspace=None,
+                                stream=None):
+    return _attention_fp8kv("hippo_draft_attention_fp8kv", CALL_DRAFT_ATTENTION, q, k_codes, v_codes, k_scale,
+                            v_scale, ctx_len, softmax_scale, num_splits, want_lse, out, workspace, stream)
 
 
 def _attention_paged(fn_name, call, q, k_pool, v_pool, block_table, ctx_len, softmax_scale, num_splits, want_lse,

@@ -91,6 +91,9 @@ struct AttnExtra {
   const int32_t* block_table = nullptr;     // paged
   int page_size = 0, max_pages = 0, n_pool_pages = 0;
   long long page_stride = 0;
+  bool fp8 = false;                         // E4M3 cache with per-(b, hk) multipliers
+  const float* k_scale = nullptr;
+  const float* v_scale = nullptr;
 };
 
 int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache, const void* v_cache,
@@ -103,8 +106,14 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr || workspace == nullptr)
     return HIPPO_ERR_NULL_ARG;
   if (append && (k_new == nullptr || v_new == nullptr)) return HIPPO_ERR_NULL_ARG;
+  if (ex.fp8 && (ex.k_scale == nullptr || ex.v_scale == nullptr)) return HIPPO_ERR_NULL_ARG;
   int rc = check_kv(kv);
   if (rc != HIPPO_OK) return rc;
+  if (ex.fp8) {
+    if (kv->dtype != HIPPO_DTYPE_BF16) return HIPPO_ERR_BAD_DTYPE;
+    // one byte per element: 16-byte rows need strides that are multiples of 16 elements
+    if (kv->stride_n % 16 || kv->stride_h % 16 || kv->stride_b % 16) return HIPPO_ERR_BAD_ALIGN;
+  }
   if (ctx_len < 0 || q_len < 1 || (long long)ctx_len + q_len > 0x7fffff00ll) return HIPPO_ERR_BAD_SHAPE;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255u))
@@ -140,6 +149,7 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   p.k_w = const_cast<void*>(k_cache); p.v_w = const_cast<void*>(v_cache);
   p.block_table = ex.block_table; p.page_shift = page_shift; p.max_pages = ex.max_pages;
   p.n_pool_pages = ex.n_pool_pages; p.page_stride = ex.page_stride;
+  p.k_scale = ex.fp8 ? ex.k_scale : nullptr; p.v_scale = ex.fp8 ? ex.v_scale : nullptr;
   const hipError_t e = launch_attention(p, kv->dtype, kv->head_dim, pl.mfma, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
 }
@@ -483,6 +493,26 @@ int hippo_draft_attention_paged(const void* q, int32_t q_len, const void* k_pool
                                 void* workspace, size_t workspace_bytes, void* stream) {
   return paged_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_pool, v_pool, block_table, kv, ctx_len,
                      softmax_scale, num_splits, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+int hippo_verify_attention_fp8kv(const void* q, int32_t q_len, const void* k_codes, const void* v_codes,
+                                 const float* k_scale, const float* v_scale, const hippo_kv_desc* kv,
+                                 int32_t ctx_len, float softmax_scale, int32_t num_splits, void* out,
+                                 float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  AttnExtra ex;
+  ex.fp8 = true; ex.k_scale = k_scale; ex.v_scale = v_scale;
+  return attention_entry(HIPPO_CALL_VERIFY_ATTENTION, q, q_len, k_codes, v_codes, kv, ctx_len, softmax_scale,
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream, ex);
+}
+
+int hippo_draft_attention_fp8kv(const void* q, int32_t q_len, const void* k_codes, const void* v_codes,
+                                const float* k_scale, const float* v_scale, const hippo_kv_desc* kv,
+                                int32_t ctx_len, float softmax_scale, int32_t num_splits, void* out,
+                                float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  AttnExtra ex;
+  ex.fp8 = true; ex.k_scale = k_scale; ex.v_scale = v_scale;
+  return attention_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_codes, v_codes, kv, ctx_len, softmax_scale,
+                         num_splits, out, lse_out, workspace, workspace_bytes, stream, ex);
 }
 
 }  // extern "C"

@@ -267,12 +267,12 @@ struct WaitLadder<0> {
 //   of a 16-lane group the j-th column of a 4 x 16 block whose rows the lanes address 4 elements at
 //   a time.  The contraction order of QK^T is likewise free: slot (ks, g, e) reads head-dim element
 //   (g*KS + ks)*8 + e of both K and Q, which makes each lane's K reads one contiguous run.
-template <int D, int TG, int TT, int NST>
+template <int D, int TG, int TT, int NST, int ES = 2>
 struct GridSmem {
-  static constexpr int kRowBytes = D * 2;
+  static constexpr int kRowBytes = D * ES;                     // a cache row: ES bytes per element
   static constexpr int kTileBytes = TT * kRowBytes;
   static constexpr int kSuperBytes = TG * 2 * kTileBytes;      // TG x (K tile, V tile)
-  static constexpr int q_bytes(int rb) { return rb * 16 * kRowBytes; }
+  static constexpr int q_bytes(int rb) { return rb * 16 * D * 2; }   // queries are always bf16
   static constexpr int stat_bytes(int rb) { return 2 * TG * rb * 16 * 4; }
   static constexpr int xbuf_bytes(int rb) { return rb * TG * (D / 16) * 1024; }   // merge staging
   static constexpr int ring_bytes(int rb) {
@@ -281,22 +281,55 @@ struct GridSmem {
   static constexpr int total(int rb) { return q_bytes(rb) + stat_bytes(rb) + ring_bytes(rb); }
 };
 
+//
+// fp8 cache (KV8): K and V rows are E4M3 codes, one byte per element, with one fp32 multiplier per
+// (batch element, KV head); queries, probabilities and the MFMA operands stay bf16.  A code becomes
+// a bf16 value exactly (4 significant bits), two per v_cvt_scalef32_pk_bf16_fp8, after the LDS read;
+// the K multiplier joins the softmax scale and the V multiplier the slice's output.  Two layout
+// changes keep the LDS reads at one instruction per operand: K operand row m of 16-token block tb
+// is tile row 8*(m/4) + 4*tb + m%4, so the 8 probabilities a lane holds belong to 8 consecutive
+// tokens 8g..8g+7, and ds_read_b64_tr_b8 (lane i of a 16-lane group addresses 8 bytes of row i/2,
+// lane j receives column j of the 8 rows) then fetches exactly those 8 tokens of V^T in one read.
+template <int D, bool KV8>
+__device__ __forceinline__ int tile_swizzle(int r) {
+  if constexpr (!KV8) return (r / (256 / (D * 2))) & (D / 8 - 1);
+  // 128-byte rows: the K reads of 16 lanes touch rows {0-3, 8-11, 16-19, 24-27} (+4), the V reads of
+  // 32 lanes 16 consecutive rows; both must spread over the 16 16-byte slots of 256 bytes
+  else if constexpr (D == 128) return ((r >> 1) ^ ((r >> 3) & 2)) & 7;
+  else return ((r >> 2) + (r >> 4)) & 3;               // 64-byte rows
+}
+
+// four E4M3 codes of one dword -> bf16, exact
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) int i32x2_t;
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+__device__ __forceinline__ bf16x8 e4m3x8_to_bf16(int lo, int hi) {
+  const bf16x2_t a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+  const bf16x2_t b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+  const bf16x2_t c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+  const bf16x2_t d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+  return __builtin_shufflevector(__builtin_shufflevector(a, b, 0, 1, 2, 3),
+                                 __builtin_shufflevector(c, d, 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // TT = tokens per tile (16 or 32), NST = ring stages (super-tiles resident in LDS)
 // MODE: 0 = contiguous cache, 1 = contiguous cache with appended-row fusion, 2 = paged cache
-template <int D, int RB, int TG, int TT, int NST, int MODE>
+template <int D, int RB, int TG, int TT, int NST, int MODE, bool KV8 = false>
 __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) {
   constexpr bool APPEND = MODE == 1, PAGED = MODE == 2;
-  using SM = GridSmem<D, TG, TT, NST>;
+  constexpr int ES = KV8 ? 1 : 2;                      // bytes per cache element
+  using SM = GridSmem<D, TG, TT, NST, ES>;
   constexpr int WAVES = RB * TG;
   constexpr int KS = D / 32;
   constexpr int DB = D / 16;
   constexpr int TB = TT / 16;                          // 16-token blocks per tile
   constexpr int ROWB = SM::kRowBytes;
-  constexpr int CPR = D / 8;
+  constexpr int CPR = ROWB / 16;                       // 16-byte chunks per cache row
   constexpr int RPI = 64 / CPR;
   constexpr int NLD = TT / RPI;                        // transfers per K (or V) tile
-  constexpr int RPS = 256 / ROWB;
-  constexpr int NQ = RB * 16 / RPI;                    // transfers for the query block
+  constexpr int QROWB = D * 2, QCPR = D / 8, QRPI = 64 / QCPR;   // the bf16 query block's layout
+  constexpr int NQ = RB * 16 / QRPI;                   // transfers for the query block
+  static_assert(!KV8 || (MODE == 0 && TT == 32), "the fp8 cache path: contiguous caches, 32-token tiles");
   constexpr int XFERS = TG * 2 * NLD;                  // transfers per super-tile
   constexpr int ISS0 = WAVES >= 8 ? 8 : (WAVES >= 4 ? 4 : (WAVES >= 2 ? 2 : 1));   // power of two <= WAVES
   constexpr int ISSUERS = XFERS < ISS0 ? XFERS : ISS0;
@@ -319,12 +352,21 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   const int b = blockIdx.z / p.n_chunks, chunk = blockIdx.z % p.n_chunks;
   const int r0 = chunk * (RB * 16);
 
+  // fp8 cache: the K multiplier scales the logits, the V multiplier the slice's output.  Fetched
+  // first, through the scalar cache (a vector load here would sit behind every K/V transfer in the
+  // same counter, and waiting for it would wait for the whole ring).
+  float k_mult = 1.f, v_mult = 1.f;
+  if constexpr (KV8) {
+    const int bh = __builtin_amdgcn_readfirstlane(b * p.Hkv + hk);
+    k_mult = p.k_scale[bh];
+    v_mult = p.v_scale[bh];
+  }
   const unsigned ring_addr = (unsigned)(uintptr_t)ring;
   const unsigned q_addr = (unsigned)(uintptr_t)Qs;
   // paged: the pools' base plus the head offset; the page and the row inside it are added per transfer
-  const char* kbase = (const char*)p.k + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * 2;
-  const char* vbase = (const char*)p.v + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * 2;
-  const long long row_bytes = p.sn * 2;
+  const char* kbase = (const char*)p.k + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * ES;
+  const char* vbase = (const char*)p.v + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * ES;
+  const long long row_bytes = p.sn * ES;
   const int ld_row = lane / CPR, ld_pc = lane % CPR;
 
   const int n_tiles = (p.n_total + TT - 1) / TT;
@@ -369,7 +411,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       if (APPEND && row >= p.ctx_len)                      // a row that has not reached the cache yet
         src = (const char*)(which ? p.v_new : p.k_new) +
               ((((long long)b * p.q_len + (row - p.ctx_len)) * p.Hkv + hk) * D) * 2;
-      dma16(src + ((ld_pc ^ ((r / RPS) & (CPR - 1))) * 16), dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
+      dma16(src + ((ld_pc ^ tile_swizzle<D, KV8>(r)) * 16), dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
     }
   };
 
@@ -384,12 +426,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     if ((n % WAVES) == wave) {
-      const int rr = n * RPI + ld_row;
+      const int rr = n * QRPI + lane / QCPR;
       int r = r0 + rr;
       r = r < p.R ? r : p.R - 1;                          // padding rows repeat the last real row
       const int i = r / p.G, gq = r % p.G;
       const char* src = (const char*)p.q + ((((long long)b * p.q_len + i) * p.H + hk * p.G + gq) * D) * 2 +
-                        ((ld_pc ^ ((rr / RPS) & (CPR - 1))) * 16);
+                        (((lane % QCPR) ^ tile_swizzle<D, false>(rr)) * 16);
       dma16(src, q_addr + n * 1024);
     }
   }
@@ -403,22 +445,42 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 #pragma unroll
   for (int db = 0; db < DB; ++db) acc[db] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const int swz_k = (j / RPS) & (CPR - 1);
-  unsigned k_off[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) k_off[ks] = j * ROWB + (((g * KS + ks) ^ swz_k) * 16);
-  const int v_row = 4 * g + (j >> 2);
-  const int swz_v = (v_row / RPS) & (CPR - 1);
+  // bf16 cache: k_off[ks] is the lane's 16-byte K operand of contraction step ks in row j (the
+  // query block uses the same offsets).  fp8 cache: a lane's KS*8 bytes of a row are NKC 16-byte
+  // chunks, and k_off[tb * NKC + c] is chunk c in the permuted row of 16-token block tb.
+  constexpr int NKC = KS / 2;
+  constexpr int NKOFF = KV8 ? TB * NKC : KS;
+  unsigned k_off[NKOFF];
   unsigned v_off[DB];
+  if constexpr (!KV8) {
+    const int swz_k = tile_swizzle<D, false>(j);
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-    v_off[db] = v_row * ROWB + (((2 * db + ((j & 3) >> 1)) ^ swz_v) * 16) + (j & 1) * 8;
+    for (int ks = 0; ks < KS; ++ks) k_off[ks] = j * ROWB + (((g * KS + ks) ^ swz_k) * 16);
+    const int v_row = 4 * g + (j >> 2);
+    const int swz_v = tile_swizzle<D, false>(v_row);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      v_off[db] = v_row * ROWB + (((2 * db + ((j & 3) >> 1)) ^ swz_v) * 16) + (j & 1) * 8;
+  } else {
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int k_row = 8 * (j >> 2) + 4 * tb + (j & 3);
+#pragma unroll
+      for (int c = 0; c < NKC; ++c)
+        k_off[tb * NKC + c] = k_row * ROWB + (((g * NKC + c) ^ tile_swizzle<D, true>(k_row)) * 16);
+    }
+    const int v_row = 8 * g + (j >> 1);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      v_off[db] = v_row * ROWB + ((db ^ tile_swizzle<D, true>(v_row)) * 16) + (j & 1) * 8;
+  }
   // keep the swizzled lane offsets in registers: left to itself the compiler recomputes them from
   // (j, g) for every tile, which costs more vector instructions than the tile's arithmetic
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(k_off[ks]));
+  for (int i = 0; i < NKOFF; ++i) asm volatile("" : "+v"(k_off[i]));
 #pragma unroll
   for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(v_off[db]));
+  const float scale_log2 = KV8 ? p.scale_log2 * k_mult : p.scale_log2;
 
   bf16x8 qop[KS];
   int trace_it = 0;
@@ -433,7 +495,9 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     if (si == 0) {
       HIPPO_TP(1)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) qop[ks] = *(const bf16x8*)(Qs + rb * 16 * ROWB + k_off[ks]);
+      for (int ks = 0; ks < KS; ++ks)
+        qop[ks] = *(const bf16x8*)(Qs + rb * 16 * QROWB + j * QROWB +
+                                   (((g * KS + ks) ^ tile_swizzle<D, false>(j)) * 16));
     }
     if (si > 0 && issued < n_super) {                      // refill the stage just vacated
       if (issuer) issue_super(issued);
@@ -450,13 +514,24 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     f32x4 s[TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) s[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    if constexpr (!KV8) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+      for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb) {
-        const bf16x8 kop = *(const bf16x8*)(Kt + tb * 16 * ROWB + k_off[ks]);
-        s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[ks], s[tb], 0, 0, 0);
-      }
+        for (int tb = 0; tb < TB; ++tb) {
+          const bf16x8 kop = *(const bf16x8*)(Kt + tb * 16 * ROWB + k_off[ks]);
+          s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[ks], s[tb], 0, 0, 0);
+        }
+    } else {
+#pragma unroll
+      for (int c = 0; c < NKC; ++c)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+          const i32x4_t kraw = *(const i32x4_t*)(Kt + k_off[tb * NKC + c]);
+          s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(kraw[0], kraw[1]), qop[2 * c], s[tb], 0, 0, 0);
+          s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(kraw[2], kraw[3]), qop[2 * c + 1], s[tb], 0, 0, 0);
+        }
+    }
     if (trace_it == 0) { HIPPO_TP(3) }
 
     if ((n0 + TT - 1) > p.ctx_len) {                     // tile touches the causal edge
@@ -464,12 +539,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if ((n0 + tb * 16 + 4 * g + e) > lim) s[tb][e] = -INFINITY;
+          if ((n0 + (KV8 ? 8 * g + 4 * tb : tb * 16 + 4 * g) + e) > lim) s[tb][e] = -INFINITY;
     }
     float m8 = fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3]));
     if (TB == 2) m8 = fmaxf(m8, fmaxf(fmaxf(s[TB - 1][0], s[TB - 1][1]), fmaxf(s[TB - 1][2], s[TB - 1][3])));
     m8 = rows4_max(m8);
-    const float mx = m8 * p.scale_log2;                    // scale > 0: max commutes with it
+    const float mx = m8 * scale_log2;                      // scale > 0: max commutes with it
     // lazy rescale: the reference m_run moves only when the tile maximum exceeds it by more than
     // kRescaleGap, so probabilities stay below 2^kRescaleGap and rescales are rare
     const bool up = mx > m_run + kRescaleGap;              // also true for the first finite maximum
@@ -486,7 +561,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     float psum = 0.f;
 #pragma unroll
     for (int e = 0; e < TB * 4; ++e) {
-      pb[e] = (__bf16)fast_exp2(fmaf(s[e >> 2][e & 3], p.scale_log2, neg_m));
+      pb[e] = (__bf16)fast_exp2(fmaf(s[e >> 2][e & 3], scale_log2, neg_m));
       psum += (float)pb[e];
     }
     l_run += psum;                                         // per-lane share; groups g meet at the end
@@ -498,12 +573,18 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       for (int e = 0; e < 8; ++e) pop[e] = pb[e % (TB * 4)];
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(Vt + v_off[db]));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(Vt + (TB - 1) * 16 * ROWB + v_off[db]));
-        const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop, acc[db], 0, 0, 0);
+        if constexpr (KV8) {
+          const i32x2_t vraw = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+              (__attribute__((address_space(3))) i32x2_t*)(Vt + v_off[db]));
+          acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(vraw[0], vraw[1]), pop, acc[db], 0, 0, 0);
+        } else {
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(Vt + v_off[db]));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(Vt + (TB - 1) * 16 * ROWB + v_off[db]));
+          const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop, acc[db], 0, 0, 0);
+        }
       }
     } else {
       typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -548,6 +629,10 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     for (int w = 0; w < TG; ++w) {
       f[w] = (mw[w] == -INFINITY) ? 0.f : fast_exp2(mw[w] - mm);
       ll = fmaf(f[w], stat_l[w * RB * 16 + rb * 16 + j], ll);
+    }
+    if constexpr (KV8) {
+#pragma unroll
+      for (int w = 0; w < TG; ++w) f[w] *= v_mult;         // after the denominator took the plain weights
     }
     const long long slot = ((long long)b * p.Hkv + hk) * p.S + split;
 #pragma unroll
@@ -676,19 +761,19 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
 // =================================================================================================
 // host launch
 // =================================================================================================
-template <int D, int RB, int TG, int TT, int NST, int MODE>
+template <int D, int RB, int TG, int TT, int NST, int MODE, bool KV8 = false>
 static hipError_t launch_grid_mode(const AttnParams& p, hipStream_t st) {
   // the paged variant keeps its slice of the page table behind the ring
-  constexpr int smem = GridSmem<D, TG, TT, NST>::total(RB) + (MODE == 2 ? kMaxSlicePages * 4 : 0);
+  constexpr int smem = GridSmem<D, TG, TT, NST, KV8 ? 1 : 2>::total(RB) + (MODE == 2 ? kMaxSlicePages * 4 : 0);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, MODE>,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid(p.S, p.Hkv, p.B * p.n_chunks);
-  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE>), grid, dim3(RB * TG * 64), smem, st, p);
+  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8>), grid, dim3(RB * TG * 64), smem, st, p);
   return hipGetLastError();
 }
 
@@ -722,6 +807,33 @@ static hipError_t launch_grid_rb(const AttnParams& p, hipStream_t st) {
   return launch_grid<D, RB, 4, 16, 3>(p, st);
 }
 
+// fp8 cache: 32-token tiles only; short slices keep the whole slice in flight (two token groups, four
+// ring stages), long ones use four groups and two stages
+template <int D, int RB>
+static hipError_t launch_kv8_rb(const AttnParams& p, hipStream_t st) {
+  const int tiles32_per_block = ((p.n_total + 31) / 32) / (p.S > 0 ? p.S : 1);
+#ifdef HIPPO_TUNE
+  if (p.variant == 20) return launch_grid_mode<D, RB, 2, 32, 4, 0, true>(p, st);
+  if (p.variant == 21) return launch_grid_mode<D, RB, 4, 32, 2, 0, true>(p, st);
+  if (p.variant == 22) return launch_grid_mode<D, RB, 4, 32, 3, 0, true>(p, st);
+  if (p.variant == 23) return launch_grid_mode<D, RB, 2, 32, 2, 0, true>(p, st);
+  if (p.variant == 24) return launch_grid_mode<D, RB, 2, 32, 3, 0, true>(p, st);
+#endif
+  if (p.variant == 1 || (p.variant != 2 && tiles32_per_block < 24))
+    return launch_grid_mode<D, RB, 2, 32, 4, 0, true>(p, st);
+  return launch_grid_mode<D, RB, 4, 32, 2, 0, true>(p, st);
+}
+
+template <int D>
+static hipError_t launch_kv8_d(const AttnParams& p, hipStream_t st) {
+  switch (p.row_chunk / 16) {
+    case 1: return launch_kv8_rb<D, 1>(p, st);
+    case 2: return launch_kv8_rb<D, 2>(p, st);
+    case 3: return launch_kv8_rb<D, 3>(p, st);
+    default: return launch_kv8_rb<D, 4>(p, st);
+  }
+}
+
 template <int D>
 static hipError_t launch_mfma_d(const AttnParams& p, hipStream_t st) {
   switch (p.row_chunk / 16) {
@@ -748,7 +860,8 @@ static hipError_t launch_combine(const AttnParams& p, hipStream_t st) {
 hipError_t launch_attention(const AttnParams& p, int dtype, int head_dim, bool use_mfma, hipStream_t st) {
   hipError_t e;
   if (dtype == HIPPO_DTYPE_BF16) {
-    if (use_mfma) e = (head_dim == 128) ? launch_mfma_d<128>(p, st) : launch_mfma_d<64>(p, st);
+    if (p.k_scale != nullptr) e = (head_dim == 128) ? launch_kv8_d<128>(p, st) : launch_kv8_d<64>(p, st);
+    else if (use_mfma) e = (head_dim == 128) ? launch_mfma_d<128>(p, st) : launch_mfma_d<64>(p, st);
     else e = (head_dim == 128) ? launch_valu<uint16_t, 128>(p, st) : launch_valu<uint16_t, 64>(p, st);
     if (e != hipSuccess) return e;
     return (head_dim == 128) ? launch_combine<uint16_t, 128>(p, st) : launch_combine<uint16_t, 64>(p, st);

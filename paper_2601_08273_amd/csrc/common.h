@@ -113,6 +113,10 @@ struct AttnParams {
   const int32_t* block_table;   // [B, max_pages]
   int page_shift, max_pages, n_pool_pages;
   long long page_stride;        // elements
+  // fp8 cache: when k_scale is set, k / v hold E4M3 codes (strides in bytes) and the cache entry is
+  // code * k_scale[b, hk] (resp. v_scale); q and out stay bf16
+  const float* k_scale;         // [B, Hkv]
+  const float* v_scale;
 };
 constexpr int kMaxSlicePages = 1024;   // page-table entries a block stages in LDS
 

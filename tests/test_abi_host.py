@@ -24,7 +24,7 @@ def lib():
 
 def test_exports_match_header(lib):
     text = open(os.path.join(ROOT, "include", "hippo.h")).read()
-    declared = set(re.findall(r"\b(hippo_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(hippo_[a-z0-9_]+)\s*\(", text))
     assert declared == set(h.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -186,6 +186,22 @@ def test_attention_append_argument_errors(lib):
         assert call(vn=None) == h.ERR_NULL_ARG
         assert call(k=None) == h.ERR_NULL_ARG
         assert call(kn=FAKE + 4) == h.ERR_BAD_ALIGN
+        assert call(q_len=0) == h.ERR_BAD_SHAPE
+        assert call(ws_bytes=64) == h.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_attention_fp8kv_argument_errors(lib):
+    for fn in (lib.hippo_verify_attention_fp8kv, lib.hippo_draft_attention_fp8kv):
+        def call(kv=None, q=FAKE, k=FAKE, v=FAKE, ks=FAKE, vs=FAKE, out=FAKE, ws=FAKE, ws_bytes=1 << 30, q_len=6,
+                 ctx=16640):
+            kv = kv or _kv()
+            return fn(q, q_len, k, v, ks, vs, C.byref(kv), ctx, 0.0, 0, out, None, ws, ws_bytes, None)
+        assert call(ks=None) == h.ERR_NULL_ARG
+        assert call(vs=None) == h.ERR_NULL_ARG
+        assert call(k=None) == h.ERR_NULL_ARG
+        assert call(_kv(dtype=h.DTYPE_F32)) == h.ERR_BAD_DTYPE              # q / out are bf16 on this path
+        assert call(_kv(stride_n=128 + 8)) == h.ERR_BAD_ALIGN               # fine for bf16, not for bytes
+        assert call(k=FAKE + 8) == h.ERR_BAD_ALIGN
         assert call(q_len=0) == h.ERR_BAD_SHAPE
         assert call(ws_bytes=64) == h.ERR_WORKSPACE_TOO_SMALL
 
