@@ -158,8 +158,8 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
       float sv = (n <= lim[x]) ? s[x] * p.scale_log2 : -INFINITY;
       float mx = sv;
 #pragma unroll
-      for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-      const float m_new = fmaxf(m_run[x], mx);
+      for (int o = 16; o > 0; o >>= 1) mx = max_nan(mx, __shfl_xor(mx, o, 64));
+      const float m_new = max_nan(m_run[x], mx);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
       const float pv = fast_exp2(sv - m_safe);
       float ps = pv;
@@ -541,9 +541,10 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
         for (int e = 0; e < 4; ++e)
           if ((n0 + (KV8 ? 8 * g + 4 * tb : tb * 16 + 4 * g) + e) > lim) s[tb][e] = -INFINITY;
     }
-    float m8 = fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3]));
-    if (TB == 2) m8 = fmaxf(m8, fmaxf(fmaxf(s[TB - 1][0], s[TB - 1][1]), fmaxf(s[TB - 1][2], s[TB - 1][3])));
-    m8 = rows4_max(m8);
+    float sv[TB * 4];
+#pragma unroll
+    for (int e = 0; e < TB * 4; ++e) sv[e] = s[e >> 2][e & 3];
+    const float m8 = rows4_max(max_nan_of(sv));
     const float mx = m8 * scale_log2;                      // scale > 0: max commutes with it
     // lazy rescale: the reference m_run moves only when the tile maximum exceeds it by more than
     // kRescaleGap, so probabilities stay below 2^kRescaleGap and rescales are rare
@@ -623,7 +624,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   {
     float mw[TG], mm = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < TG; ++w) { mw[w] = stat_m[w * RB * 16 + rb * 16 + j]; mm = fmaxf(mm, mw[w]); }
+    for (int w = 0; w < TG; ++w) { mw[w] = stat_m[w * RB * 16 + rb * 16 + j]; mm = max_nan(mm, mw[w]); }
     float f[TG], ll = 0.f;
 #pragma unroll
     for (int w = 0; w < TG; ++w) {
@@ -710,11 +711,11 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
     const float m0 = tid < p.S ? p.part_m[(slot0 + tid) * p.R + r] : -INFINITY;
     const float l0 = tid < p.S ? p.part_l[(slot0 + tid) * p.R + r] : 0.f;
     float mloc = m0;
-    for (int s2 = tid + 256; s2 < p.S; s2 += 256) mloc = fmaxf(mloc, p.part_m[(slot0 + s2) * p.R + r]);
+    for (int s2 = tid + 256; s2 < p.S; s2 += 256) mloc = max_nan(mloc, p.part_m[(slot0 + s2) * p.R + r]);
     mloc = wave_max(mloc);
     if ((tid & 63) == 0) red[tid >> 6] = mloc;
     __syncthreads();
-    mstar = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    mstar = max_nan(max_nan(red[0], red[1]), max_nan(red[2], red[3]));
     float dloc = 0.f;
     if (tid < p.S) {
       const float w = (m0 == -INFINITY) ? 0.f : fast_exp2(m0 - mstar);

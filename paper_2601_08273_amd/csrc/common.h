@@ -49,10 +49,24 @@ template <> struct Elem<uint16_t> {  // bf16 bits
   }
 };
 
+// Maximum that propagates NaN (IEEE 754-2019 "maximum").  Unlike fmaxf it needs no quieting of its
+// inputs, which the compiler otherwise performs with one extra instruction per operand that comes
+// out of an MFMA, and nested calls fold into the three-input v_maximum3_f32.
+__device__ __forceinline__ float max_nan(float a, float b) { return __builtin_elementwise_maximum(a, b); }
+// maximum of N register values as a chain of three-input maxima: (N + 1) / 2 instructions
+template <int N>
+__device__ __forceinline__ float max_nan_of(const float (&v)[N]) {
+  float m = v[0];
+#pragma unroll
+  for (int i = 1; i + 1 < N; i += 2) m = max_nan(max_nan(m, v[i]), v[i + 1]);
+  if ((N - 1) % 2) m = max_nan(m, v[N - 1]);
+  return m;
+}
+
 // ---- wavefront reductions (results valid in every lane) --------------------------------------
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  for (int o = 32; o > 0; o >>= 1) v = max_nan(v, __shfl_xor(v, o, 64));
   return v;
 }
 __device__ __forceinline__ float wave_sum(float v) {
@@ -68,9 +82,9 @@ __device__ __forceinline__ float wave_sum(float v) {
 // crossbar (ds_bpermute) per step.
 __device__ __forceinline__ float rows4_max(float v) {
   auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  v = max_nan(__uint_as_float(a[0]), __uint_as_float(a[1]));
   auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+  return max_nan(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ __forceinline__ float rows4_sum(float v) {
   auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);

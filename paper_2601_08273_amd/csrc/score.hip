@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
       if (PASS == 1) {
         float mx = sv;
 #pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        for (int o = 16; o > 0; o >>= 1) mx = max_nan(mx, __shfl_xor(mx, o, 64));
         float ps = fast_exp2(sv - mx);      // the tile always holds at least one valid token
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
@@ -259,11 +259,10 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
             for (int e = 0; e < 4; ++e)
               if (!tok_ok[tb][e]) z[tb][e] = -INFINITY;
         }
-        float mx = -INFINITY;                   // the scale is positive: take the max of the raw logits
+        float zv[TBW * 4];                      // the scale is positive: take the max of the raw logits
 #pragma unroll
-        for (int tb = 0; tb < TBW; ++tb)
-          mx = fmaxf(mx, fmaxf(fmaxf(z[tb][0], z[tb][1]), fmaxf(z[tb][2], z[tb][3])));
-        mx = rows4_max(mx);
+        for (int e = 0; e < TBW * 4; ++e) zv[e] = z[e >> 2][e & 3];
+        float mx = rows4_max(max_nan_of(zv));
         mx *= scale_log2;
         const float neg_m = (mx == -INFINITY) ? 0.f : -mx;
         float ps = 0.f;
@@ -297,7 +296,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
       for (int rr = tid; rr < RDEF && base + rr < Rs && base + rr < r0 + RCH; rr += NT) {
         float mm = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) mm = fmaxf(mm, wm_s[w][rr]);
+        for (int w = 0; w < NW; ++w) mm = max_nan(mm, wm_s[w][rr]);
         float ll = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w)
@@ -349,7 +348,7 @@ __global__ __launch_bounds__(256) void sattn_row_lse(ScoreParams p) {
       }
       float mx = mm;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) mx = fmaxf(mx, m[u]);
+      for (int u = 0; u < 8; ++u) mx = max_nan(mx, m[u]);
       if (mx != -INFINITY) {
         ll *= fast_exp2(mm - mx);                 // mm = -inf: ll is 0 and exp2(-inf) = 0
 #pragma unroll
@@ -364,7 +363,7 @@ __global__ __launch_bounds__(256) void sattn_row_lse(ScoreParams p) {
   if (slice == 0 && row < rows) {
     float mx = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) mx = fmaxf(mx, sm[u][rl]);
+    for (int u = 0; u < 8; ++u) mx = max_nan(mx, sm[u][rl]);
     float tot = 0.f;
 #pragma unroll
     for (int u = 0; u < 8; ++u) tot += (sm[u][rl] != -INFINITY) ? sl[u][rl] * fast_exp2(sm[u][rl] - mx) : 0.f;
