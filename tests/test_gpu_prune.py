@@ -47,6 +47,9 @@ def test_score_on_configs(hippo, name):
     (1, 70, 7, 1, 128, 3, 13, 21, 8, 8, (5, 5)),   # 819 tokens: several tiles and a ragged tail
     (2, 5, 4, 4, 64, 4, 8, 8, 1, 0, (8, 8)),       # 64-token crops (the maximum)
     (1, 4, 4, 2, 64, 2, 33, 32, 5, 3, (5, 5)),     # 1056-token frames: beyond the register-resident fusion
+    (2, 9, 8, 2, 128, 5, 16, 16, 6, 4, (5, 5)),    # 256-token frames: one token tile each
+    (2, 6, 4, 2, 64, 3, 16, 32, 0, 1, (5, 5)),     # 512-token frames: two tiles per frame
+    (1, 5, 4, 1, 64, 3, 32, 32, 2, 0, (4, 8)),     # 1024-token frames: four tiles, two values per thread
 ])
 def test_score_random_shapes(hippo, dtype, shape):
     B, L, H, Hkv, d, F, gh, gw, off, tail, (ch, cw) = shape
@@ -58,6 +61,24 @@ def test_score_random_shapes(hippo, dtype, shape):
     kv = k[:, :, off:off + nv].reshape(B, Hkv, F, gh, gw, d)
     kv += 0.8 * np.roll(kv, 1, axis=2) + 0.5 * np.roll(kv, 1, axis=4)
     score_case(hippo, q, k, off, F, gh, gw, dtype, ch, cw, what="%s %s" % (dtype, shape))
+
+
+def test_score_is_repeatable_bit_for_bit(hippo):
+    """The 16K configuration and a four-layer call, repeated: every partial result has one writer and
+    the sums have a fixed order, so each repetition must give the same bits whatever the order in
+    which blocks run."""
+    cfg = si.CONFIGS["c3_16k"]
+    x = si.make_inputs(cfg, 3)
+    dt, n = cfg.dtype, cfg.ctx_len
+    q, k = dev(x["q_txt"], dt), dev(x["k"][:, :, :n], dt)
+    vid = hippo.video_desc(cfg.n_frames, cfg.grid_h, cfg.grid_w, cfg.n_prefix)
+    first = hippo.hippo_score_tokens(q, k, vid).clone()
+    first4 = hippo.hippo_score_tokens_layers([q] * 4, [k] * 4, vid, emb_layer=0).clone()
+    for _ in range(25):
+        assert torch.equal(hippo.hippo_score_tokens(q, k, vid), first)
+        assert torch.equal(hippo.hippo_score_tokens_layers([q] * 4, [k] * 4, vid, emb_layer=0), first4)
+    rs, _ = oracle.score_tokens(x["q_txt"], x["k"][:, :, :n], cfg.n_prefix, cfg.n_frames, cfg.grid_h, cfg.grid_w)
+    assert_close(host(first), rs, dt, "16K fused")
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
