@@ -50,7 +50,14 @@ enum hippo_status {
   HIPPO_ERR_HIP = 6                  /* a HIP runtime call (launch) failed */
 };
 
-enum hippo_dtype { HIPPO_DTYPE_F32 = 0, HIPPO_DTYPE_BF16 = 1 };
+enum hippo_dtype {
+  HIPPO_DTYPE_F32 = 0,
+  HIPPO_DTYPE_BF16 = 1,
+  /* 8-bit floating-point CACHE elements (E4M3, see hippo_verify_attention_fp8kv): one byte each.
+   * Accepted by the *_fp8kv attention calls, by hippo_select_gather_kv (rows are byte copies) and by
+   * hippo_workspace_bytes for those calls; every other call answers BAD_DTYPE. */
+  HIPPO_DTYPE_FP8_E4M3 = 2
+};
 
 enum hippo_call {
   HIPPO_CALL_SCORE_TOKENS = 0,
@@ -163,7 +170,8 @@ int hippo_score_tokens_layers(int32_t n_layers, const void* const* q_txt_layers,
  *                   [vis_offset + N_v, src_len), for K and V and every KV head, bit copies.
  * scores [B, N_v] fp32.  1 <= k <= N_v.  src/dst descriptors must agree in batch, n_kv_heads,
  * head_dim and dtype (strides may differ); dst holds src_len - N_v + k rows.  k_src/v_src may be a
- * different model's cache than the one that was scored.  k_dst/v_dst may be NULL together to get
+ * different model's cache than the one that was scored, and may be an 8-bit cache
+ * (HIPPO_DTYPE_FP8_E4M3: the kept rows' codes are copied; the per-head multipliers stay valid).  k_dst/v_dst may be NULL together to get
  * the indices only.  src and dst must not overlap.
  * Errors: NULL_ARG, BAD_SHAPE (k out of range, video span outside src_len, descriptor mismatch),
  *         BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
@@ -235,11 +243,12 @@ int hippo_draft_attention_append(const void* q, int32_t q_len, const void* k_new
  * 0x7f / 0xff are NaN), one byte per element, laid out as kv describes with strides counted in
  * elements = bytes (multiples of 16).  k_scale / v_scale are DEVICE arrays [B, H_kv] of fp32
  * multipliers, all > 0: the cache entry is multiplier * decoded code.  kv->dtype must be
- * HIPPO_DTYPE_BF16: it is the type of q and out.  The result is that of hippo_verify_attention /
+ * HIPPO_DTYPE_FP8_E4M3, the type of the cache; q and out are bf16.  The result is that of hippo_verify_attention /
  * hippo_draft_attention on the dequantised cache, computed with the same arithmetic as the bf16 path
  * (codes convert to bf16 exactly; the K multiplier joins the softmax scale, the V multiplier the
  * output).  Workspace: hippo_workspace_bytes with the same kv.  Caches are read only.
- * Errors: as hippo_verify_attention, plus NULL_ARG for the multipliers, BAD_DTYPE unless bf16.
+ * Errors: as hippo_verify_attention, plus NULL_ARG for the multipliers, BAD_DTYPE for any other
+ * cache type.
  */
 int hippo_verify_attention_fp8kv(const void* q, int32_t q_len, const void* k_codes, const void* v_codes,
                                  const float* k_scale, const float* v_scale, const hippo_kv_desc* kv,

@@ -13,7 +13,7 @@ from typing import Optional, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhippo.so")
 
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3 = 0, 1, 2
 CALL_SCORE_TOKENS, CALL_SELECT_GATHER_KV, CALL_DRAFT_ATTENTION, CALL_VERIFY_ATTENTION = 0, 1, 2, 3
 SCORE_ATTN, SCORE_TEMP, SCORE_SPA, SCORE_ALL, SCORE_ACCUMULATE_ONLY = 1, 2, 4, 7, 8
 OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = range(7)
@@ -144,7 +144,9 @@ def _dtype_code(t) -> int:
         return DTYPE_F32
     if t.dtype == torch.bfloat16:
         return DTYPE_BF16
-    raise TypeError("unsupported dtype %s (fp32 or bf16)" % t.dtype)
+    if t.dtype in (torch.uint8, torch.float8_e4m3fn):       # E4M3 cache codes
+        return DTYPE_FP8_E4M3
+    raise TypeError("unsupported dtype %s (fp32, bf16, or uint8 / float8_e4m3fn cache codes)" % t.dtype)
 
 
 def _ptr(t) -> Optional[int]:
@@ -337,7 +339,7 @@ def _attention_fp8kv(fn_name, call, q, k_codes, v_codes, k_scale, v_scale, ctx_l
     Hkv = k_codes.shape[1]
     for t in (k_scale, v_scale):
         assert t.shape == (B, Hkv) and t.is_contiguous() and t.dtype == torch.float32
-    kv = KvDesc(B, H, Hkv, d, DTYPE_BF16, k_codes.stride(0), k_codes.stride(1), k_codes.stride(2))
+    kv = KvDesc(B, H, Hkv, d, DTYPE_FP8_E4M3, k_codes.stride(0), k_codes.stride(1), k_codes.stride(2))
     nbytes = workspace_bytes(call, kv, None, q_len, ctx_len + q_len, 0, num_splits)
     ws = _workspace(nbytes, q.device, workspace)
     if out is None:

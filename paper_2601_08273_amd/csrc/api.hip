@@ -11,11 +11,16 @@ namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-inline int elem_bytes(int dtype) { return dtype == HIPPO_DTYPE_BF16 ? 2 : 4; }
+inline int elem_bytes(int dtype) {
+  return dtype == HIPPO_DTYPE_FP8_E4M3 ? 1 : (dtype == HIPPO_DTYPE_BF16 ? 2 : 4);
+}
 
-int check_kv(const hippo_kv_desc* kv) {
+// allow_fp8: the call takes 8-bit caches (the fp8 attention calls, the gather, their workspace query)
+int check_kv(const hippo_kv_desc* kv, bool allow_fp8 = false) {
   if (kv == nullptr) return HIPPO_ERR_NULL_ARG;
-  if (kv->dtype != HIPPO_DTYPE_F32 && kv->dtype != HIPPO_DTYPE_BF16) return HIPPO_ERR_BAD_DTYPE;
+  if (kv->dtype != HIPPO_DTYPE_F32 && kv->dtype != HIPPO_DTYPE_BF16 &&
+      !(allow_fp8 && kv->dtype == HIPPO_DTYPE_FP8_E4M3))
+    return HIPPO_ERR_BAD_DTYPE;
   if (kv->batch < 1 || kv->n_kv_heads < 1 || kv->n_q_heads < 1) return HIPPO_ERR_BAD_SHAPE;
   if (kv->n_q_heads % kv->n_kv_heads != 0) return HIPPO_ERR_BAD_SHAPE;
   if (kv->head_dim != 64 && kv->head_dim != 128) return HIPPO_ERR_BAD_SHAPE;
@@ -47,7 +52,7 @@ int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, in
   const int G = kv->n_q_heads / kv->n_kv_heads;
   if ((long long)G * q_len > 4096) return HIPPO_ERR_BAD_SHAPE;
   pl->R = G * q_len;
-  pl->mfma = kv->dtype == HIPPO_DTYPE_BF16;
+  pl->mfma = kv->dtype != HIPPO_DTYPE_F32;   // bf16 and 8-bit caches
   int tile, min_tiles_per_block;
   if (pl->mfma) {
     pl->row_chunk = pl->R >= 64 ? 64 : (pl->R + 15) / 16 * 16;
@@ -107,13 +112,9 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
     return HIPPO_ERR_NULL_ARG;
   if (append && (k_new == nullptr || v_new == nullptr)) return HIPPO_ERR_NULL_ARG;
   if (ex.fp8 && (ex.k_scale == nullptr || ex.v_scale == nullptr)) return HIPPO_ERR_NULL_ARG;
-  int rc = check_kv(kv);
+  int rc = check_kv(kv, ex.fp8);
   if (rc != HIPPO_OK) return rc;
-  if (ex.fp8) {
-    if (kv->dtype != HIPPO_DTYPE_BF16) return HIPPO_ERR_BAD_DTYPE;
-    // one byte per element: 16-byte rows need strides that are multiples of 16 elements
-    if (kv->stride_n % 16 || kv->stride_h % 16 || kv->stride_b % 16) return HIPPO_ERR_BAD_ALIGN;
-  }
+  if (ex.fp8 != (kv->dtype == HIPPO_DTYPE_FP8_E4M3)) return HIPPO_ERR_BAD_DTYPE;
   if (ctx_len < 0 || q_len < 1 || (long long)ctx_len + q_len > 0x7fffff00ll) return HIPPO_ERR_BAD_SHAPE;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255u))
@@ -150,7 +151,9 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   p.block_table = ex.block_table; p.page_shift = page_shift; p.max_pages = ex.max_pages;
   p.n_pool_pages = ex.n_pool_pages; p.page_stride = ex.page_stride;
   p.k_scale = ex.fp8 ? ex.k_scale : nullptr; p.v_scale = ex.fp8 ? ex.v_scale : nullptr;
-  const hipError_t e = launch_attention(p, kv->dtype, kv->head_dim, pl.mfma, static_cast<hipStream_t>(stream));
+  // q and out of the 8-bit cache calls are bf16
+  const int io_dtype = ex.fp8 ? (int)HIPPO_DTYPE_BF16 : kv->dtype;
+  const hipError_t e = launch_attention(p, io_dtype, kv->head_dim, pl.mfma, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
 }
 
@@ -230,7 +233,7 @@ const char* hippo_status_string(int status) {
 size_t hippo_workspace_bytes(int32_t call, const hippo_kv_desc* kv, const hippo_video_desc* vid,
                              int32_t n_rows, int32_t seq_len, int32_t k, int32_t num_splits) {
   (void)k;
-  if (check_kv(kv) != HIPPO_OK) return 0;
+  if (check_kv(kv, call != HIPPO_CALL_SCORE_TOKENS) != HIPPO_OK) return 0;
   switch (call) {
     case HIPPO_CALL_SCORE_TOKENS: {
       ScorePlan pl;
@@ -344,7 +347,7 @@ int hippo_select_gather_kv(const float* scores, int32_t k, const void* k_src, co
   if (do_gather && (k_dst == nullptr || v_dst == nullptr || k_src == nullptr || v_src == nullptr))
     return HIPPO_ERR_NULL_ARG;
   if (src == nullptr) return HIPPO_ERR_NULL_ARG;
-  if ((rc = check_kv(src)) != HIPPO_OK) return rc;
+  if ((rc = check_kv(src, true)) != HIPPO_OK) return rc;
   if (workspace_bytes < 256) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
   SelectParams p;
   p.scores = scores; p.B = src->batch; p.Nv = (int)Nv; p.k = k; p.idx_out = idx_out;
@@ -355,7 +358,7 @@ int hippo_select_gather_kv(const float* scores, int32_t k, const void* k_src, co
   p.src_len = src_len; p.dst_len = 0; p.vis_off = vid->vis_offset;
   if (do_gather) {
     if (dst == nullptr) return HIPPO_ERR_NULL_ARG;
-    if ((rc = check_kv(dst)) != HIPPO_OK) return rc;
+    if ((rc = check_kv(dst, true)) != HIPPO_OK) return rc;
     if (dst->batch != src->batch || dst->n_kv_heads != src->n_kv_heads || dst->head_dim != src->head_dim ||
         dst->dtype != src->dtype)
       return HIPPO_ERR_BAD_SHAPE;

@@ -191,19 +191,36 @@ def test_attention_append_argument_errors(lib):
 
 
 def test_attention_fp8kv_argument_errors(lib):
+    fp8 = dict(dtype=h.DTYPE_FP8_E4M3)
     for fn in (lib.hippo_verify_attention_fp8kv, lib.hippo_draft_attention_fp8kv):
         def call(kv=None, q=FAKE, k=FAKE, v=FAKE, ks=FAKE, vs=FAKE, out=FAKE, ws=FAKE, ws_bytes=1 << 30, q_len=6,
                  ctx=16640):
-            kv = kv or _kv()
+            kv = kv or _kv(**fp8)
             return fn(q, q_len, k, v, ks, vs, C.byref(kv), ctx, 0.0, 0, out, None, ws, ws_bytes, None)
         assert call(ks=None) == h.ERR_NULL_ARG
         assert call(vs=None) == h.ERR_NULL_ARG
         assert call(k=None) == h.ERR_NULL_ARG
-        assert call(_kv(dtype=h.DTYPE_F32)) == h.ERR_BAD_DTYPE              # q / out are bf16 on this path
-        assert call(_kv(stride_n=128 + 8)) == h.ERR_BAD_ALIGN               # fine for bf16, not for bytes
+        assert call(_kv(dtype=h.DTYPE_F32)) == h.ERR_BAD_DTYPE              # the descriptor names the cache type
+        assert call(_kv(dtype=h.DTYPE_BF16)) == h.ERR_BAD_DTYPE
+        assert call(_kv(stride_n=128 + 8, **fp8)) == h.ERR_BAD_ALIGN        # fine for bf16, not for bytes
         assert call(k=FAKE + 8) == h.ERR_BAD_ALIGN
         assert call(q_len=0) == h.ERR_BAD_SHAPE
         assert call(ws_bytes=64) == h.ERR_WORKSPACE_TOO_SMALL
+    # 8-bit caches exist for the fp8 attention calls and the gather only
+    kv8, vid = _kv(**fp8), h.video_desc(64, 16, 16, 128)
+    assert _verify(lib, kv8) == h.ERR_BAD_DTYPE
+    assert _verify(lib, kv8, fn="hippo_draft_attention") == h.ERR_BAD_DTYPE
+    assert lib.hippo_verify_attention_append(FAKE, 6, FAKE, FAKE, FAKE, FAKE, C.byref(kv8), 16640, 0.0, 0, FAKE, None,
+                                             FAKE, 1 << 30, None) == h.ERR_BAD_DTYPE
+    assert h.workspace_bytes(h.CALL_SCORE_TOKENS, kv8, vid, 128, 16646) == 0
+    need = h.workspace_bytes(h.CALL_VERIFY_ATTENTION, kv8, None, 6, 16646)
+    assert need > 0 and need == h.workspace_bytes(h.CALL_VERIFY_ATTENTION, _kv(), None, 6, 16646)
+    assert h.workspace_bytes(h.CALL_SELECT_GATHER_KV, kv8, vid, 0, 16646, 1639) == 256
+    # gather of an 8-bit cache: descriptors must agree, rows must stay 16-byte aligned
+    sel = lambda src, dst: lib.hippo_select_gather_kv(FAKE, 1639, FAKE, FAKE, C.byref(src), 16646, C.byref(vid), FAKE,
+                                                       FAKE, C.byref(dst), FAKE, FAKE, 256, None)
+    assert sel(kv8, _kv()) == h.ERR_BAD_SHAPE                                 # 8-bit source, bf16 destination
+    assert sel(kv8, _kv(stride_n=128 + 8, **fp8)) == h.ERR_BAD_ALIGN
 
 
 def test_attention_paged_argument_errors(lib):

@@ -130,3 +130,35 @@ def test_full_size(hippo, name):
     cfg = si.CONFIGS[name]
     x = si.make_inputs(cfg, 0)
     run_case(hippo, x["q_new"], x["k"], x["v"], cfg.ctx_len, 0, what=name)
+
+
+def test_prune_then_draft_attention_on_an_fp8_cache(hippo):
+    """The draft path with an 8-bit cache end to end: the gather copies the kept rows' codes (bit
+    exact, the per-head multipliers stay valid), and the draft attention over the pruned codes equals
+    the oracle's attention over the same rows of the dequantised cache."""
+    cfg = si.CONFIGS["draft"]
+    x = si.make_inputs(cfg, 4)
+    n = cfg.ctx_len + 1                                   # context + the draft token's own row
+    kc, km = si.quantize_e4m3(x["k"][:, :, :n])
+    vc, vm = si.quantize_e4m3(x["v"][:, :, :n])
+    r = np.random.default_rng(0)
+    scores = r.standard_normal((cfg.batch, cfg.n_visual)).astype(np.float32)
+    k_keep = (cfg.n_visual * cfg.keep_pct + 99) // 100
+    vid = hippo.video_desc(cfg.n_frames, cfg.grid_h, cfg.grid_w, cfg.n_prefix)
+    idx, kp, vp = hippo.hippo_select_gather_kv(torch.from_numpy(scores).cuda(), k_keep, codes_dev(kc), codes_dev(vc),
+                                               vid, cfg.n_q_heads)
+    torch.cuda.synchronize()
+    ridx = oracle.topk(scores, k_keep)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
+    rows = np.concatenate([np.arange(cfg.n_prefix), cfg.n_prefix + ridx[0],
+                           np.arange(cfg.n_prefix + cfg.n_visual, n)])
+    assert cfg.batch == 1
+    np.testing.assert_array_equal(kp.cpu().numpy(), kc[:, :, rows])
+    np.testing.assert_array_equal(vp.cpu().numpy(), vc[:, :, rows])
+    q = prep(x["q_new"][:, :1], "bf16")
+    ctx = len(rows) - 1
+    out = hippo.hippo_draft_attention_fp8kv(dev(q, "bf16"), kp, vp, torch.from_numpy(km).cuda(),
+                                            torch.from_numpy(vm).cuda(), ctx)
+    torch.cuda.synchronize()
+    ro, _ = oracle.attention_fp8kv(q, kc[:, :, rows], vc[:, :, rows], km, vm, ctx)
+    assert_close(host(out), ro, "bf16", "draft attention over the pruned fp8 cache")
