@@ -26,7 +26,8 @@
  *    private to the call until the stream has passed it.
  *  - Data pointers must be 16-byte aligned; strides are in elements and must keep every row
  *    16-byte aligned (multiples of 8 for bf16, of 4 for fp32).  head_dim is 64 or 128.
- *  - dtype: HIPPO_DTYPE_F32 or HIPPO_DTYPE_BF16 for q / K / V / emb / attention outputs.  Scores,
+ *  - dtype: HIPPO_DTYPE_F32 or HIPPO_DTYPE_BF16 for q / K / V / emb / attention outputs (plus the
+ *    8-bit cache type of the *_fp8kv calls and the gather, see enum hippo_dtype).  Scores,
  *    attention mass and log-sum-exp are always fp32, indices int32.  Accumulation is fp32;
  *    bf16 outputs are rounded to nearest even.
  */
@@ -44,7 +45,7 @@ enum hippo_status {
   HIPPO_OK = 0,
   HIPPO_ERR_NULL_ARG = 1,            /* a required pointer is NULL */
   HIPPO_ERR_BAD_SHAPE = 2,           /* a size, count, stride or index range is invalid */
-  HIPPO_ERR_BAD_DTYPE = 3,           /* dtype is not one of the two supported */
+  HIPPO_ERR_BAD_DTYPE = 3,           /* dtype is not one the call supports */
   HIPPO_ERR_BAD_ALIGN = 4,           /* a pointer or stride breaks the 16-byte rule */
   HIPPO_ERR_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes below hippo_workspace_bytes(...) */
   HIPPO_ERR_HIP = 6                  /* a HIP runtime call (launch) failed */
