@@ -557,21 +557,23 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       for (int db = 0; db < DB; ++db) acc[db] *= a;
     }
     const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
-    // the PV product sees P rounded to bf16; the denominator sums the same rounded values
-    __bf16 pb[TB * 4];
+    // the PV product sees P rounded to bf16; the denominator sums the same rounded values.  Two
+    // probabilities are rounded by one packed conversion and read back with a shift and a mask.
+    unsigned pk[TB * 2];
     float psum = 0.f;
 #pragma unroll
-    for (int e = 0; e < TB * 4; ++e) {
-      pb[e] = (__bf16)fast_exp2(fmaf(s[e >> 2][e & 3], scale_log2, neg_m));
-      psum += (float)pb[e];
+    for (int h = 0; h < TB * 2; ++h) {
+      typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+      const f32x2_t x = {fast_exp2(fmaf(s[h >> 1][(2 * h) & 3], scale_log2, neg_m)),
+                         fast_exp2(fmaf(s[h >> 1][(2 * h + 1) & 3], scale_log2, neg_m))};
+      pk[h] = __builtin_bit_cast(unsigned, __builtin_convertvector(x, bf16x2_t));
+      psum += __uint_as_float(pk[h] << 16) + __uint_as_float(pk[h] & 0xffff0000u);
     }
     l_run += psum;                                         // per-lane share; groups g meet at the end
     if (trace_it == 0) { HIPPO_TP(4) }
 
     if (TB == 2) {
-      bf16x8 pop;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pop[e] = pb[e % (TB * 4)];
+      const bf16x8 pop = __builtin_bit_cast(bf16x8, (i32x4_t){(int)pk[0], (int)pk[1], (int)pk[2 % (TB * 2)], (int)pk[3 % (TB * 2)]});
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         if constexpr (KV8) {
@@ -588,11 +590,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
         }
       }
     } else {
-      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-      bf16x4 pop4;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pop4[e] = pb[e];
-      const s16x4 pop = __builtin_bit_cast(s16x4, pop4);
+      const s16x4 pop = __builtin_bit_cast(s16x4, (i32x2_t){(int)pk[0], (int)pk[1]});
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         const s16x4 vop = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
