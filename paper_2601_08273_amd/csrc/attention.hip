@@ -8,6 +8,9 @@
 //   * attn_partial_grid  -- bf16, MFMA 16x16x32: S^T = K Q^T puts the streamed tokens on the MFMA
 //     M axis, so the score tile comes out in exactly the register layout the PV product
 //     O^T = V^T P^T needs for its B operand; only V goes through a transposing LDS read.
+//     Instantiations of the same kernel cover the cache-format variants: rows appended by the
+//     launch itself, paged caches, and caches of 8-bit floating-point codes (converted to bf16
+//     after the LDS read).
 //   * attn_partial_valu  -- fp32 or bf16 inputs, fp32 vector ALU; used for fp32 caches.
 #include "common.h"
 
