@@ -12,6 +12,8 @@
 //     launch itself, paged caches, and caches of 8-bit floating-point codes (converted to bf16
 //     after the LDS read).
 //   * attn_partial_valu  -- fp32 or bf16 inputs, fp32 vector ALU; used for fp32 caches.
+#include <type_traits>
+
 #include "common.h"
 
 // Phase timestamps for kernel tuning: compiled in only when HIPPO_TRACE is defined (never in the
@@ -617,12 +619,22 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   __syncthreads();   // (a) every wave is done reading the ring before anyone overwrites it
   HIPPO_TP(7)
   // a wave finishes head-dim blocks tg, tg + TG, ...: those stay in its registers, only the blocks
-  // that other waves finish go through LDS
+  // that other waves finish go through LDS.  The body is instantiated once per value of tg (it is
+  // wave-uniform), so which blocks stay and which travel is known at compile time: straight-line
+  // code whose LDS reads all go out before the first one is needed.
+  const long long slot = ((long long)b * p.Hkv + hk) * p.S + split;
+  auto finish = [&](auto tgc) {
+    constexpr int TGC = decltype(tgc)::value;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-    if (db % TG != tg) xbuf[(wave * DB + db) * 64 + lane] = acc[db];
-  __syncthreads();   // (b) accumulators and statistics of all waves visible
-  {
+    for (int db = 0; db < DB; ++db)
+      if (db % TG != TGC) xbuf[(wave * DB + db) * 64 + lane] = acc[db];
+    __syncthreads();   // (b) accumulators and statistics of all waves visible
+    f32x4 other[TG][DB / TG];                                // [source wave group][own head-dim block]
+#pragma unroll
+    for (int w = 0; w < TG; ++w)
+#pragma unroll
+      for (int dd = 0; dd < DB / TG; ++dd)
+        if (w != TGC) other[w][dd] = xbuf[((w * RB + rb) * DB + TGC + TG * dd) * 64 + lane];
     float mw[TG], mm = -INFINITY;
 #pragma unroll
     for (int w = 0; w < TG; ++w) { mw[w] = stat_m[w * RB * 16 + rb * 16 + j]; mm = max_nan(mm, mw[w]); }
@@ -636,23 +648,27 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 #pragma unroll
       for (int w = 0; w < TG; ++w) f[w] *= v_mult;         // after the denominator took the plain weights
     }
-    const long long slot = ((long long)b * p.Hkv + hk) * p.S + split;
 #pragma unroll
     for (int dd = 0; dd < DB / TG; ++dd) {
-      const int db = tg + TG * dd;
+      const int db = TGC + TG * dd;
       f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int w = 0; w < TG; ++w) {
-        if (w == tg) o += acc[w + TG * dd] * f[w];                        // tg is wave-uniform
-        else o += xbuf[((w * RB + rb) * DB + db) * 64 + lane] * f[w];
+        if (w == TGC) o += acc[TGC + TG * dd] * f[w];
+        else o += other[w][dd] * f[w];
       }
       if (row < p.R) *(f32x4*)(p.part_o + (slot * p.R + row) * D + db * 16 + 4 * g) = o;
     }
-    if (tg == 0 && g == 0 && row < p.R) {
+    if (TGC == 0 && g == 0 && row < p.R) {
       p.part_m[slot * p.R + row] = mm;
       p.part_l[slot * p.R + row] = ll;
     }
-  }
+  };
+  static_assert(TG == 2 || TG == 4, "token groups");
+  if (tg == 0) finish(std::integral_constant<int, 0>());
+  else if (tg == 1) finish(std::integral_constant<int, 1>());
+  else if (tg == 2) finish(std::integral_constant<int, 2 % TG>());
+  else finish(std::integral_constant<int, 3 % TG>());
   HIPPO_TP(8)
   HIPPO_TP_FLUSH
   if (APPEND && split == 0 && chunk == 0) append_new_rows<uint16_t, D>(p, b, hk);
