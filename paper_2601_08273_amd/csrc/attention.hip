@@ -12,6 +12,7 @@
 //     launch itself, paged caches, and caches of 8-bit floating-point codes (converted to bf16
 //     after the LDS read).
 //   * attn_partial_valu  -- fp32 or bf16 inputs, fp32 vector ALU; used for fp32 caches.
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -783,12 +784,17 @@ template <int D, int RB, int TG, int TT, int NST, int MODE, bool KV8 = false>
 static hipError_t launch_grid_mode(const AttnParams& p, hipStream_t st) {
   // the paged variant keeps its slice of the page table behind the ring
   constexpr int smem = GridSmem<D, TG, TT, NST, KV8 ? 1 : 2>::total(RB) + (MODE == 2 ? kMaxSlicePages * 4 : 0);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  // the attribute belongs to a (kernel, device) pair: set it once for each device this process uses
+  static std::atomic<unsigned long long> attr_set{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (!(attr_set.load(std::memory_order_acquire) & bit)) {
+    e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.fetch_or(bit, std::memory_order_release);
   }
   dim3 grid(p.S, p.Hkv, p.B * p.n_chunks);
   hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8>), grid, dim3(RB * TG * 64), smem, st, p);
