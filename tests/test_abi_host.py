@@ -30,6 +30,16 @@ def test_exports_match_header(lib):
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, without warnings."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "hippo.h"\nint main(void) { return (int)sizeof(hippo_kv_desc) == 0; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_struct_layout_matches_header():
     assert C.sizeof(h.KvDesc) == 48 and h.KvDesc.stride_b.offset == 24
     assert C.sizeof(h.VideoDesc) == 24
