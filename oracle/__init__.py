@@ -227,6 +227,27 @@ def e4m3_decode(codes: np.ndarray) -> np.ndarray:
     return sign * val
 
 
+def quantize_e4m3(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """[B,Hkv,N,d] -> (E4M3 codes uint8 of the same shape, multipliers float32 [B,Hkv]).
+    Per (batch element, KV head): multiplier = max|x| / 448 in float32 (1 when the maximum is 0);
+    code = the E4M3 value nearest to x / multiplier (float32 division), ties to the even code
+    (the rule of IEEE 754 applied to the format's 3-bit mantissa).  Written out as a search over the
+    decoded magnitudes, whose order is the order of their codes."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    amax = np.abs(x).max(axis=(2, 3)).astype(np.float32)
+    mult = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    y = (x / mult[:, :, None, None]).astype(np.float32)
+    mags = e4m3_decode(np.arange(127, dtype=np.uint8))          # 0 .. 448, increasing
+    a = np.abs(y).astype(np.float64)
+    hi = np.clip(np.searchsorted(mags, a, side="left"), 1, 126)
+    lo = hi - 1
+    d_lo, d_hi = a - mags[lo], mags[hi] - a
+    pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    code = np.where(a >= 448.0, np.uint8(126), code)             # the maximum maps to the largest code
+    return (code | (np.signbit(y).astype(np.uint8) << 7)).astype(np.uint8), mult
+
+
 def attention_fp8kv(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray, k_scale: np.ndarray,
                     v_scale: np.ndarray, ctx_len: int, scale: Optional[float] = None
                     ) -> Tuple[np.ndarray, np.ndarray]:

@@ -102,3 +102,46 @@ def test_multiplier_identities():
     ones = np.full_like(vc, 0x38)
     o, _ = oracle.attention_fp8kv(q, kc, ones, km, vm, ctx)
     np.testing.assert_allclose(o, np.broadcast_to(np.repeat(vm, G, axis=1)[:, None, :, None], o.shape), rtol=1e-12)
+
+
+def test_quantizer_closed_forms_and_ties():
+    # one head whose maximum is exactly 448: the multiplier is 1 and x itself is encoded
+    x = np.zeros((1, 1, 1, 16), np.float32)
+    x[0, 0, 0, :12] = [448.0, 1.0, 1.0625, 1.1875, 1.03, -1.09, 2.0 ** -9, 2.0 ** -10, 1.5 * 2.0 ** -9, 0.0, -0.0, 464.0 - 448.0]
+    codes, mult = oracle.quantize_e4m3(x)
+    assert mult[0, 0] == 1.0
+    c = codes[0, 0, 0]
+    assert c[0] == 0x7E and c[1] == 0x38
+    assert c[2] == 0x38            # 1.0625 lies midway between 1.0 (0x38) and 1.125 (0x39): the even code
+    assert c[3] == 0x3A            # 1.1875 lies midway between 1.125 (0x39) and 1.25 (0x3a): the even code
+    assert c[4] == 0x38 and c[5] == 0xB9
+    assert c[6] == 0x01            # the smallest subnormal
+    assert c[7] == 0x00            # half of it: a tie between 0 and 0x01, the even code
+    assert c[8] == 0x02            # 1.5 subnormal steps: a tie between 0x01 and 0x02
+    assert c[9] == 0x00 and c[10] == 0x80
+    assert c[11] == 0x58           # 16.0
+    # an all-zero head keeps multiplier 1
+    z, m = oracle.quantize_e4m3(np.zeros((1, 2, 3, 16), np.float32))
+    assert np.all(z == 0) and np.all(m == 1.0)
+
+
+def test_quantizer_equals_library_conversion():
+    r = np.random.default_rng(5)
+    x = (r.standard_normal((2, 3, 257, 64)) * r.uniform(0.01, 50, (2, 3, 1, 1))).astype(np.float32)
+    x[0, 0, :5] = 0.0
+    codes, mult = oracle.quantize_e4m3(x)
+    amax = np.abs(x).max(axis=(2, 3))
+    np.testing.assert_array_equal(mult, (amax / np.float32(448.0)).astype(np.float32))
+    y = torch.from_numpy((x / mult[:, :, None, None]).astype(np.float32))
+    lib = y.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(codes, lib)
+    # and the input generator's quantiser is the same function
+    c2, m2 = si.quantize_e4m3(x)
+    np.testing.assert_array_equal(c2, codes)
+    np.testing.assert_array_equal(m2, mult)
+    # every code is a nearest neighbour
+    table = oracle.e4m3_decode(np.arange(256, dtype=np.uint8))
+    finite = table[~np.isnan(table)]
+    yv = y.numpy().astype(np.float64)
+    best = np.abs(yv[..., None][:1, :1, :50] - finite).min(axis=-1)
+    np.testing.assert_allclose(np.abs(oracle.e4m3_decode(codes)[:1, :1, :50] - yv[:1, :1, :50]), best, atol=0)
