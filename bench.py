@@ -187,12 +187,14 @@ def main():
 
     # fp8 cache: the same rows as E4M3 codes with one multiplier per (batch element, KV head)
     have_fp8 = dt == "bf16"
-    if have_fp8:
-        def to_codes(x):
-            mult = (x.float().abs().amax(dim=(2, 3)) / 448.0).clamp_min(1e-30)
-            codes = (x.float() / mult[:, :, None, None]).clamp_(-448.0, 448.0).to(torch.float8_e4m3fn)
-            return codes, mult.contiguous()
-        k8, v8 = [to_codes(kd[l]) for l in range(L)], [to_codes(vd[l]) for l in range(L)]
+    if have_fp8:                                     # written by the library's own quantiser
+        q8 = [h.hippo_quantize_kv_e4m3(kd[l], vd[l]) for l in range(L)]
+        k8, v8 = [(c[0], c[2]) for c in q8], [(c[1], c[3]) for c in q8]
+        ws_q8 = torch.empty(int(h.load().hippo_quantize_kv_workspace_bytes(C.byref(kvd), n_tot)), dtype=torch.uint8,
+                            device="cuda")
+
+    def quantize_layer0():
+        h.hippo_quantize_kv_e4m3(kd[0], vd[0], k_codes=k8[0][0], v_codes=v8[0][0], workspace=ws_q8)
 
     def verify_fp8_all():
         for l in range(L):
@@ -264,6 +266,7 @@ def main():
     run_copy_verify = capture(copy_then_verify_all)
     run_verify_paged = capture(verify_paged_all)
     run_verify_fp8 = capture(verify_fp8_all) if have_fp8 else None
+    run_quantize = capture(quantize_layer0) if have_fp8 else None
     run_layers_one = capture(score_layers_one_call)
     run_layers_acc = capture(score_layers_accumulate)
     run_sd_sampling = capture(spec_sampling)
@@ -319,6 +322,7 @@ def main():
     t_copy_verify = alone(run_copy_verify) / L
     t_verify_paged = alone(run_verify_paged) / L
     t_verify_fp8 = alone(run_verify_fp8) / L if have_fp8 else None
+    t_quantize = alone(run_quantize) if have_fp8 else None
     t_layers_one = alone(run_layers_one)
     t_layers_acc = alone(run_layers_acc)
     t_sd_sampling = alone(run_sd_sampling) / SD_REPS
@@ -369,6 +373,7 @@ def main():
                "alone:copy_new_rows_then_verify_per_layer": round(t_copy_verify * 1e6, 3),
                "alone:verify_paged(16-token pages)_per_layer": round(t_verify_paged * 1e6, 3),
                "alone:verify_fp8_cache_per_layer": round(t_verify_fp8 * 1e6, 3) if have_fp8 else None,
+               "alone:quantize_one_layer_cache_to_fp8": round(t_quantize * 1e6, 2) if have_fp8 else None,
                "alone:score_%d_layers(one call)" % NLS: round(t_layers_one * 1e6, 2),
                "alone:score_%d_layers(accumulate calls)" % NLS: round(t_layers_acc * 1e6, 2),
                "alone:spec_verify(sampling, V=%d)" % V: round(t_sd_sampling * 1e6, 2),

@@ -8,7 +8,7 @@
  *                        hippo_verify_attention (+ hippo_workspace_bytes, hippo_status_string).
  * Built around it:       hippo_score_tokens_layers (Eq. 2's layer sum in one call),
  *                        hippo_*_attention_append, hippo_*_attention_paged and
- *                        hippo_*_attention_fp8kv (cache-format variants),
+ *                        hippo_*_attention_fp8kv with hippo_quantize_kv_e4m3 (cache-format variants),
  *                        hippo_spec_verify (the speculative-sampling verdict of Eq. 1),
  *                        hippo_vpsd_* (host-side control of the parallel decoding rounds).
  *
@@ -261,6 +261,25 @@ int hippo_draft_attention_fp8kv(const void* q, int32_t q_len, const void* k_code
                                 int32_t ctx_len, float softmax_scale, int32_t num_splits,
                                 void* out, float* lse_out,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Writer of that 8-bit cache format: rows [0, n_rows) of a bf16 or fp32 cache become E4M3 codes and
+ * one multiplier per (batch element, KV head), separately for K and V:
+ *     multiplier = max|x| / 448 over the head's n_rows x d entries (fp32; 1 when the maximum is 0)
+ *     code       = the E4M3 value nearest to x / multiplier (fp32 division), ties to the even code
+ * so the largest entry of every head maps to the largest code and nothing overflows.  src describes
+ * k_src / v_src (dtype F32 or BF16), dst the code arrays (dtype FP8_E4M3, strides in bytes); both
+ * agree in batch, n_kv_heads, head_dim.  k_scale / v_scale [B, H_kv] fp32 are OUTPUTS.  Inputs must
+ * be finite (a NaN or infinity gives unspecified codes for its head).  Deterministic.  Workspace:
+ * hippo_quantize_kv_workspace_bytes(src, n_rows).
+ * Errors: NULL_ARG, BAD_DTYPE, BAD_SHAPE (descriptor mismatch, n_rows < 1), BAD_ALIGN,
+ *         WORKSPACE_TOO_SMALL, HIP.
+ */
+size_t hippo_quantize_kv_workspace_bytes(const hippo_kv_desc* src, int32_t n_rows);
+int hippo_quantize_kv_e4m3(const void* k_src, const void* v_src, const hippo_kv_desc* src, int32_t n_rows,
+                           void* k_codes, void* v_codes, const hippo_kv_desc* dst,
+                           float* k_scale, float* v_scale,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The same two attention calls over a PAGED cache (a cache-format variant for serving stacks that

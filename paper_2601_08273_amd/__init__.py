@@ -24,6 +24,7 @@ EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
            "hippo_verify_attention_append", "hippo_draft_attention_append",
            "hippo_verify_attention_paged", "hippo_draft_attention_paged",
            "hippo_verify_attention_fp8kv", "hippo_draft_attention_fp8kv",
+           "hippo_quantize_kv_workspace_bytes", "hippo_quantize_kv_e4m3",
            "hippo_spec_verify_workspace_bytes", "hippo_spec_verify", "hippo_vpsd_prefill_buffer",
            "hippo_vpsd_init", "hippo_vpsd_plan", "hippo_vpsd_commit", "hippo_vpsd_simulate")
 VPSD_CONSERVATIVE, VPSD_OPTIMISTIC = 0, 1
@@ -108,6 +109,10 @@ def load():
                lib.hippo_verify_attention_fp8kv, lib.hippo_draft_attention_fp8kv):
         fn.argtypes = [vp, i32, vp, vp, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
+    lib.hippo_quantize_kv_workspace_bytes.argtypes = [kvp, i32]
+    lib.hippo_quantize_kv_workspace_bytes.restype = C.c_size_t
+    lib.hippo_quantize_kv_e4m3.argtypes = [vp, vp, kvp, i32, vp, vp, kvp, vp, vp, vp, sz, vp]
+    lib.hippo_quantize_kv_e4m3.restype = C.c_int
     f64 = C.c_double
     lib.hippo_vpsd_prefill_buffer.argtypes = [f64, f64, f64]
     lib.hippo_vpsd_prefill_buffer.restype = C.c_int32
@@ -365,6 +370,31 @@ def hippo_draft_attention_fp8kv(q, k_codes, v_codes, k_scale, v_scale, ctx_len: 
                                 stream=None):
     return _attention_fp8kv("hippo_draft_attention_fp8kv", CALL_DRAFT_ATTENTION, q, k_codes, v_codes, k_scale,
                             v_scale, ctx_len, softmax_scale, num_splits, want_lse, out, workspace, stream)
+
+
+def hippo_quantize_kv_e4m3(k_src, v_src, n_rows: Optional[int] = None, k_codes=None, v_codes=None, workspace=None,
+                           stream=None):
+    """k_src / v_src [B,Hkv,N,d] bf16 or fp32 -> (k_codes, v_codes uint8 [B,Hkv,n_rows,d], k_scale, v_scale
+    fp32 [B,Hkv]): the cache format of the *_fp8kv attention calls."""
+    torch = _torch()
+    lib = load()
+    B, Hkv, N, d = k_src.shape
+    n_rows = N if n_rows is None else n_rows
+    assert v_src.shape == k_src.shape and v_src.stride() == k_src.stride() and 1 <= n_rows <= N
+    src = kv_desc(k_src, Hkv)
+    if k_codes is None:
+        k_codes = torch.empty((B, Hkv, n_rows, d), dtype=torch.uint8, device=k_src.device)
+        v_codes = torch.empty_like(k_codes)
+    assert k_codes.shape[:2] == (B, Hkv) and k_codes.shape[3] == d and k_codes.shape[2] >= n_rows
+    assert v_codes.shape == k_codes.shape and v_codes.stride() == k_codes.stride()
+    dst = kv_desc(k_codes, Hkv)
+    k_scale = torch.empty((B, Hkv), dtype=torch.float32, device=k_src.device)
+    v_scale = torch.empty_like(k_scale)
+    ws = _workspace(int(lib.hippo_quantize_kv_workspace_bytes(C.byref(src), n_rows)), k_src.device, workspace)
+    st = lib.hippo_quantize_kv_e4m3(_ptr(k_src), _ptr(v_src), C.byref(src), n_rows, _ptr(k_codes), _ptr(v_codes),
+                                    C.byref(dst), _ptr(k_scale), _ptr(v_scale), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "hippo_quantize_kv_e4m3")
+    return k_codes, v_codes, k_scale, v_scale
 
 
 def _attention_paged(fn_name, call, q, k_pool, v_pool, block_table, ctx_len, softmax_scale, num_splits, want_lse,

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhippo.so")
-SOURCES = ["api.hip", "attention.hip", "score.hip", "select_gather.hip", "spec_verify.hip", "vpsd.cpp"]
+SOURCES = ["api.hip", "attention.hip", "quantize.hip", "score.hip", "select_gather.hip", "spec_verify.hip", "vpsd.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instruction forms

@@ -518,4 +518,37 @@ int hippo_draft_attention_fp8kv(const void* q, int32_t q_len, const void* k_code
                          num_splits, out, lse_out, workspace, workspace_bytes, stream, ex);
 }
 
+size_t hippo_quantize_kv_workspace_bytes(const hippo_kv_desc* src, int32_t n_rows) {
+  if (check_kv(src) != HIPPO_OK || n_rows < 1) return 0;
+  return align_up((size_t)src->batch * src->n_kv_heads * 2 * quant_slices(n_rows, src->head_dim) * sizeof(float), 256);
+}
+
+int hippo_quantize_kv_e4m3(const void* k_src, const void* v_src, const hippo_kv_desc* src, int32_t n_rows,
+                           void* k_codes, void* v_codes, const hippo_kv_desc* dst, float* k_scale, float* v_scale,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (k_src == nullptr || v_src == nullptr || k_codes == nullptr || v_codes == nullptr || k_scale == nullptr ||
+      v_scale == nullptr || workspace == nullptr)
+    return HIPPO_ERR_NULL_ARG;
+  int rc = check_kv(src);
+  if (rc != HIPPO_OK) return rc;
+  if ((rc = check_kv(dst, true)) != HIPPO_OK) return rc;
+  if (dst->dtype != HIPPO_DTYPE_FP8_E4M3) return HIPPO_ERR_BAD_DTYPE;
+  if (dst->batch != src->batch || dst->n_kv_heads != src->n_kv_heads || dst->head_dim != src->head_dim || n_rows < 1)
+    return HIPPO_ERR_BAD_SHAPE;
+  if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_codes) || !aligned16(v_codes) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255u) || (reinterpret_cast<uintptr_t>(k_scale) & 3u) ||
+      (reinterpret_cast<uintptr_t>(v_scale) & 3u))
+    return HIPPO_ERR_BAD_ALIGN;
+  if (workspace_bytes < hippo_quantize_kv_workspace_bytes(src, n_rows)) return HIPPO_ERR_WORKSPACE_TOO_SMALL;
+  QuantParams p;
+  p.k_src = k_src; p.v_src = v_src; p.k_dst = k_codes; p.v_dst = v_codes; p.k_scale = k_scale; p.v_scale = v_scale;
+  p.partial = reinterpret_cast<float*>(workspace);
+  p.B = src->batch; p.Hkv = src->n_kv_heads; p.D = src->head_dim; p.n_rows = n_rows;
+  p.n_slices = quant_slices(n_rows, src->head_dim); p.src_dtype = src->dtype;
+  p.ssb = src->stride_b; p.ssh = src->stride_h; p.ssn = src->stride_n;
+  p.dsb = dst->stride_b; p.dsh = dst->stride_h; p.dsn = dst->stride_n;
+  const hipError_t e = launch_quantize(p, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HIPPO_OK : HIPPO_ERR_HIP;
+}
+
 }  // extern "C"

@@ -185,6 +185,21 @@ struct SelectParams {
 };
 hipError_t launch_select_gather(const SelectParams& p, hipStream_t st);
 
+// ---- writer of the 8-bit cache format -----------------------------------------------------------
+struct QuantParams {
+  const void* k_src;
+  const void* v_src;
+  void* k_dst;            // E4M3 codes
+  void* v_dst;
+  float* k_scale;         // [B, Hkv] multipliers (outputs)
+  float* v_scale;
+  float* partial;         // workspace: [B, Hkv, 2, n_slices] slice maxima
+  int B, Hkv, D, n_rows, n_slices, src_dtype;
+  long long ssb, ssh, ssn, dsb, dsh, dsn;   // element strides (dst: bytes)
+};
+int quant_slices(int n_rows, int head_dim);
+hipError_t launch_quantize(const QuantParams& p, hipStream_t st);
+
 // ---- speculative-sampling verification ---------------------------------------------------------
 constexpr int kSdSeg = 8192;        // vocabulary entries handled by one block
 constexpr int kSdMaxGamma = 64;     // longest draft chain

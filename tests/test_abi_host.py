@@ -233,6 +233,28 @@ def test_attention_fp8kv_argument_errors(lib):
     assert sel(kv8, _kv(stride_n=128 + 8, **fp8)) == h.ERR_BAD_ALIGN
 
 
+def test_quantize_argument_errors(lib):
+    src, dst = _kv(), _kv(dtype=h.DTYPE_FP8_E4M3)
+    need = lib.hippo_quantize_kv_workspace_bytes(C.byref(src), 16646)
+    assert need > 0 and need % 256 == 0
+    assert lib.hippo_quantize_kv_workspace_bytes(C.byref(src), 0) == 0
+    assert lib.hippo_quantize_kv_workspace_bytes(C.byref(dst), 100) == 0        # the source is bf16 or fp32
+
+    def call(k=FAKE, v=FAKE, s=src, n=16646, kc=FAKE, vc=FAKE, d=dst, ks=FAKE, vs=FAKE, ws=FAKE, ws_bytes=need):
+        return lib.hippo_quantize_kv_e4m3(k, v, C.byref(s), n, kc, vc, C.byref(d), ks, vs, ws, ws_bytes, None)
+    assert call(k=None) == h.ERR_NULL_ARG
+    assert call(vc=None) == h.ERR_NULL_ARG
+    assert call(ks=None) == h.ERR_NULL_ARG
+    assert call(ws=None) == h.ERR_NULL_ARG
+    assert call(s=dst) == h.ERR_BAD_DTYPE
+    assert call(d=src) == h.ERR_BAD_DTYPE
+    assert call(d=_kv(dtype=h.DTYPE_FP8_E4M3, n_kv_heads=2, n_q_heads=28)) == h.ERR_BAD_SHAPE
+    assert call(n=0) == h.ERR_BAD_SHAPE
+    assert call(kc=FAKE + 4) == h.ERR_BAD_ALIGN
+    assert call(d=_kv(dtype=h.DTYPE_FP8_E4M3, stride_n=128 + 8)) == h.ERR_BAD_ALIGN
+    assert call(ws_bytes=need - 1) == h.ERR_WORKSPACE_TOO_SMALL
+
+
 def test_attention_paged_argument_errors(lib):
     def desc(**kw):
         d = dict(batch=1, n_q_heads=28, n_kv_heads=4, head_dim=128, dtype=h.DTYPE_BF16, page_size=16, max_pages=1100,

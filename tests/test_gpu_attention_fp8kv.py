@@ -162,3 +162,55 @@ def test_prune_then_draft_attention_on_an_fp8_cache(hippo):
     torch.cuda.synchronize()
     ro, _ = oracle.attention_fp8kv(q, kc[:, :, rows], vc[:, :, rows], km, vm, ctx)
     assert_close(host(out), ro, "bf16", "draft attention over the pruned fp8 cache")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 64), (2, 3, 77, 64), (1, 4, 1670, 128), (2, 2, 5000, 128)])
+def test_quantize_kv_bit_exact(hippo, dtype, shape):
+    """The library's writer of the 8-bit format against the oracle's: codes and multipliers bit for bit
+    (values spread over eight octaves per head, planted zeros, ties and the subnormal range)."""
+    B, Hkv, N, d = shape
+    r = np.random.default_rng(N)
+    mag = np.exp2(r.uniform(-9, 8, (B, Hkv, N, d)))
+    k = prep(r.standard_normal(shape) * mag, dtype)
+    v = prep(r.standard_normal(shape) * r.uniform(0.05, 20, (B, Hkv, 1, 1)), dtype)
+    k[:, :, ::7, ::5] = 0.0
+    v[0, 0] = 0.0                                           # an all-zero head: multiplier 1, codes 0
+    if N > 8:
+        # one head whose maximum is exactly 448: the values themselves are encoded, ties included
+        k[0, -1] = np.clip(k[0, -1], -400, 400)
+        k[0, -1, 0, :8] = [448.0, 1.0625, 1.1875, -1.0625, 2.0 ** -10, 1.5 * 2.0 ** -9, 2.5 * 2.0 ** -9, -0.0]
+    kd, vd = dev(k, dtype), dev(v, dtype)
+    kc, vc, ks, vs = hippo.hippo_quantize_kv_e4m3(kd, vd)
+    torch.cuda.synchronize()
+    rk, rkm = oracle.quantize_e4m3(k)
+    rv, rvm = oracle.quantize_e4m3(v)
+    np.testing.assert_array_equal(ks.cpu().numpy(), rkm)
+    np.testing.assert_array_equal(vs.cpu().numpy(), rvm)
+    np.testing.assert_array_equal(kc.cpu().numpy(), rk)
+    np.testing.assert_array_equal(vc.cpu().numpy(), rv)
+
+
+def test_quantize_strided_prefix_then_attend(hippo):
+    """Quantise the first n rows of caches that sit interleaved in one allocation, into a larger code
+    buffer, then attend over the codes: equals the oracle's attention over its own quantisation."""
+    B, ql, H, Hkv, d, ctx = 2, 3, 8, 2, 128, 300
+    q, k, v = rand_case(21, B, ql, H, Hkv, d, ctx)
+    q, k, v = prep(q, "bf16"), prep(k, "bf16"), prep(v, "bf16")
+    n = ctx + ql
+    buf = torch.zeros((B, Hkv, n + 9, 2, d), dtype=torch.bfloat16, device="cuda")
+    buf[:, :, :n, 0] = dev(k, "bf16")
+    buf[:, :, :n, 1] = dev(v, "bf16")
+    buf[:, :, n:] = 1000.0                                   # rows beyond n must not reach the maximum
+    codes = torch.full((B, Hkv, n + 20, 2, d), 0x7F, dtype=torch.uint8, device="cuda")
+    kc, vc, ks, vs = hippo.hippo_quantize_kv_e4m3(buf[:, :, :, 0], buf[:, :, :, 1], n_rows=n,
+                                                  k_codes=codes[:, :, :, 0], v_codes=codes[:, :, :, 1])
+    out = hippo.hippo_verify_attention_fp8kv(dev(q, "bf16"), kc, vc, ks, vs, ctx)
+    torch.cuda.synchronize()
+    rk, rkm = oracle.quantize_e4m3(k)
+    rv, rvm = oracle.quantize_e4m3(v)
+    np.testing.assert_array_equal(kc[:, :, :n].cpu().numpy(), rk)
+    np.testing.assert_array_equal(ks.cpu().numpy(), rkm)
+    assert torch.all(codes[:, :, n:] == 0x7F)                # nothing written past n_rows
+    ro, _ = oracle.attention_fp8kv(q, rk, rv, rkm, rvm, ctx)
+    assert_close(host(out), ro, "bf16", "attention over the library's own quantisation")
