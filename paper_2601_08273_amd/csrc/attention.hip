@@ -375,9 +375,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   const long long row_bytes = p.sn * ES;
   const int ld_row = lane / CPR, ld_pc = lane % CPR;
 
+  // the tiles are dealt to the S slices as evenly as possible, the first n_tiles % S slices taking
+  // one more (32-bit arithmetic: this runs before the first transfer can be issued)
   const int n_tiles = (p.n_total + TT - 1) / TT;
-  const int t_lo = (int)((long long)split * n_tiles / p.S);
-  const int t_hi = (int)((long long)(split + 1) * n_tiles / p.S);
+  const int tq = n_tiles / p.S, tr = n_tiles % p.S;
+  const int t_lo = split * tq + min(split, tr);
+  const int t_hi = t_lo + tq + (split < tr ? 1 : 0);
   const int n_blk = t_hi - t_lo;                           // tiles of this block
   const int n_super = (n_blk + TG - 1) / TG;
 
