@@ -47,7 +47,7 @@ struct AttnPlan {
 };
 
 int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, int num_splits, AttnPlan* pl) {
-  (void)call;   // draft and verify share one heuristic today
+  (void)call;   // draft and verify share one launch heuristic today
   if (q_len < 1 || n_total < q_len || num_splits < 0) return HIPPO_ERR_BAD_SHAPE;
   const int G = kv->n_q_heads / kv->n_kv_heads;
   if ((long long)G * q_len > 4096) return HIPPO_ERR_BAD_SHAPE;
@@ -146,6 +146,7 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)kv->head_dim);
   p.scale_log2 = scale * kLog2e;
   p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks; p.variant = 0;
+  p.wave_prio = call == HIPPO_CALL_VERIFY_ATTENTION ? 1 : 0;
   p.k_new = append ? k_new : nullptr; p.v_new = append ? v_new : nullptr;
   p.k_w = const_cast<void*>(k_cache); p.v_w = const_cast<void*>(v_cache);
   p.block_table = ex.block_table; p.page_shift = page_shift; p.max_pages = ex.max_pages;

@@ -344,6 +344,9 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   static_assert(DB % TG == 0, "head-dim blocks must split over the token groups");
   static_assert(TT == 16 || TT == 32, "tile size");
 
+  // verification is the critical path of a decoding round: its waves win the issue arbitration
+  // against the draft call's waves that share a compute unit with them
+  if (p.wave_prio) __builtin_amdgcn_s_setprio(2);
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Qs = smem;
   float* stat_m = (float*)(smem + SM::q_bytes(RB));          // [TG][RB*16]
