@@ -3,9 +3,14 @@
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
 import this package.  It never touches the HIP library and the HIP binding never touches it.
 
-The wrapper does argument marshalling only, plus the two input re-arrangements the boundary
-defines (the "embedding = visual keys concatenated over KV heads" default, and slicing the
-visual span out of a cache); all arithmetic is in the C file.
+For the paper's own path the wrapper does argument marshalling only, plus the two input
+re-arrangements the boundary defines (the "embedding = visual keys concatenated over KV heads"
+default, and slicing the visual span out of a cache); that arithmetic is in the C file.  The 8-bit
+cache format, which the paper does not mention, is written out here in numpy (float64):
+`e4m3_decode`, `quantize_e4m3`, and `attention_fp8kv` over the dequantised cache through a dense
+restatement of the attention definition (`_attention64`).  Pins: tests/test_oracle_pins.py,
+tests/test_oracle_sd_pins.py, tests/test_oracle_fp8_pins.py; nothing here is "parity unpinned"
+except against the authors' own code, which does not exist in public form.
 """
 from __future__ import annotations
 
