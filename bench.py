@@ -35,7 +35,6 @@ from concurrent.futures import ThreadPoolExecutor
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 
@@ -68,7 +67,7 @@ def main():
 
     import paper_2601_08273_amd as h
     import synth_inputs as si
-    from gpu_util import dev
+    from parity_util import dev
 
     h.load()                                   # fails loudly if libhippo.so is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"

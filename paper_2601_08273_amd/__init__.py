@@ -6,6 +6,7 @@ is no fallback path.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes as C
 import os
 from typing import Optional, Tuple
@@ -181,6 +182,29 @@ def workspace_bytes(call: int, kv: KvDesc, vid: Optional[VideoDesc], n_rows: int
                                             n_rows, seq_len, k, num_splits))
 
 
+def _on(stream):
+    """Context in which the wrapper allocates what the caller did not pass (workspace, outputs): the
+    stream the kernels are enqueued on.  torch's caching allocator ties a block to the stream that was
+    current when it was allocated and may hand it out again, on that stream, as soon as the tensor is
+    dropped; allocated under another stream than the kernels', a workspace could be recycled while they
+    still use it."""
+    return _torch().cuda.stream(stream) if stream is not None else contextlib.nullcontext()
+
+
+def _allocates_on_its_stream(fn):
+    """Run the marshalling of `fn` with its `stream=` argument as the current stream (see _on)."""
+    import functools
+    import inspect
+    sig = inspect.signature(fn)
+
+    @functools.wraps(fn)
+    def wrapper(*args, **kwargs):
+        stream = sig.bind(*args, **kwargs).arguments.get("stream")
+        with _on(stream):
+            return fn(*args, **kwargs)
+    return wrapper
+
+
 def _workspace(nbytes: int, device, workspace=None):
     torch = _torch()
     if workspace is not None:
@@ -197,6 +221,7 @@ def _check(status: int, what: str):
 # the four entry points
 # ---------------------------------------------------------------------------------------------
 
+@_allocates_on_its_stream
 def hippo_score_tokens(q_txt, k_cache, vid: VideoDesc, emb=None, flags: int = SCORE_ALL,
                        attn_mass_inout=None, want_components: bool = False, scores_out=None, workspace=None,
                        stream=None):
@@ -224,6 +249,7 @@ def hippo_score_tokens(q_txt, k_cache, vid: VideoDesc, emb=None, flags: int = SC
     return (scores, comps) if want_components else scores
 
 
+@_allocates_on_its_stream
 def hippo_score_tokens_layers(q_txt_layers, k_cache_layers, vid: VideoDesc, emb_layer: int = 0, emb=None,
                               flags: int = SCORE_ALL, attn_mass_inout=None, want_components: bool = False,
                               scores_out=None, workspace=None, stream=None):
@@ -257,6 +283,7 @@ def hippo_score_tokens_layers(q_txt_layers, k_cache_layers, vid: VideoDesc, emb_
     return (scores, comps) if want_components else scores
 
 
+@_allocates_on_its_stream
 def hippo_select_gather_kv(scores, k: int, k_src, v_src, vid: VideoDesc, n_q_heads: Optional[int] = None,
                            gather: bool = True, idx_out=None, k_dst=None, v_dst=None, workspace=None, stream=None):
     """scores [B,N_v] fp32 -> (idx [B,k] int32, k_dst, v_dst [B,Hkv,N-N_v+k,d]).
@@ -288,6 +315,7 @@ def hippo_select_gather_kv(scores, k: int, k_src, v_src, vid: VideoDesc, n_q_hea
     return idx, k_dst, v_dst
 
 
+@_allocates_on_its_stream
 def _attention(fn_name, call, q, k_cache, v_cache, ctx_len, softmax_scale, num_splits, want_lse, out,
                workspace, stream, k_new=None, v_new=None):
     torch = _torch()
@@ -333,6 +361,7 @@ def hippo_draft_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: floa
                       softmax_scale, num_splits, want_lse, out, workspace, stream, k_new, v_new)
 
 
+@_allocates_on_its_stream
 def _attention_fp8kv(fn_name, call, q, k_codes, v_codes, k_scale, v_scale, ctx_len, softmax_scale, num_splits,
                      want_lse, out, workspace, stream):
     torch = _torch()
@@ -372,6 +401,7 @@ def hippo_draft_attention_fp8kv(q, k_codes, v_codes, k_scale, v_scale, ctx_len: 
                             v_scale, ctx_len, softmax_scale, num_splits, want_lse, out, workspace, stream)
 
 
+@_allocates_on_its_stream
 def hippo_quantize_kv_e4m3(k_src, v_src, n_rows: Optional[int] = None, k_codes=None, v_codes=None, workspace=None,
                            stream=None):
     """k_src / v_src [B,Hkv,N,d] bf16 or fp32 -> (k_codes, v_codes uint8 [B,Hkv,n_rows,d], k_scale, v_scale
@@ -397,6 +427,7 @@ def hippo_quantize_kv_e4m3(k_src, v_src, n_rows: Optional[int] = None, k_codes=N
     return k_codes, v_codes, k_scale, v_scale
 
 
+@_allocates_on_its_stream
 def _attention_paged(fn_name, call, q, k_pool, v_pool, block_table, ctx_len, softmax_scale, num_splits, want_lse,
                      out, workspace, stream):
     torch = _torch()
@@ -434,6 +465,7 @@ def hippo_draft_attention_paged(q, k_pool, v_pool, block_table, ctx_len: int, so
                             ctx_len, softmax_scale, num_splits, want_lse, out, workspace, stream)
 
 
+@_allocates_on_its_stream
 def hippo_spec_verify(p_logits, q_logits, draft_tokens, u_accept, u_sample, temperature: float,
                       want_alpha: bool = False, n_accept_out=None, next_token_out=None, workspace=None,
                       stream=None):

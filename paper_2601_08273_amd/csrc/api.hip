@@ -36,6 +36,7 @@ int check_video(const hippo_video_desc* v) {
   if (v == nullptr) return HIPPO_ERR_NULL_ARG;
   if (v->n_frames < 1 || v->grid_h < 1 || v->grid_w < 1 || v->vis_offset < 0) return HIPPO_ERR_BAD_SHAPE;
   if ((long long)v->n_frames * v->grid_h * v->grid_w > (1ll << 30)) return HIPPO_ERR_BAD_SHAPE;
+  if (v->n_frames > 65535) return HIPPO_ERR_BAD_SHAPE;   // frames are a y dimension of the crop kernels' grids
   return HIPPO_OK;
 }
 
@@ -145,7 +146,7 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   p.sb = kv->stride_b; p.sh = kv->stride_h; p.sn = kv->stride_n;
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)kv->head_dim);
   p.scale_log2 = scale * kLog2e;
-  p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks; p.variant = 0;
+  p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks;
   p.wave_prio = call == HIPPO_CALL_VERIFY_ATTENTION ? 1 : 0;
   p.k_new = append ? k_new : nullptr; p.v_new = append ? v_new : nullptr;
   p.k_w = const_cast<void*>(k_cache); p.v_w = const_cast<void*>(v_cache);
@@ -176,6 +177,8 @@ int plan_score(const hippo_kv_desc* kv, const hippo_video_desc* vid, int l_txt, 
   const size_t row_lse = align_up(rows * sizeof(float), 256);
   pl->n_rsplit = score_row_splits(kv->dtype, (long long)pl->n_tile * kv->n_kv_heads * kv->batch * n_layers,
                                   l_txt * (kv->n_q_heads / kv->n_kv_heads));
+  // launch limits of the sweep (KV heads x row runs on grid y) and of the row merge (32 rows per block)
+  if ((long long)kv->n_kv_heads * pl->n_rsplit > 65535 || rows / 32 >= (1ull << 31)) return HIPPO_ERR_BAD_SHAPE;
   const size_t col = align_up((size_t)kv->batch * n_layers * kv->n_kv_heads * pl->n_rsplit * Nv * sizeof(float), 256);
   const size_t vec = align_up((size_t)kv->batch * Nv * sizeof(float), 256);
   size_t o = 0;
@@ -536,6 +539,7 @@ int hippo_quantize_kv_e4m3(const void* k_src, const void* v_src, const hippo_kv_
   if (dst->dtype != HIPPO_DTYPE_FP8_E4M3) return HIPPO_ERR_BAD_DTYPE;
   if (dst->batch != src->batch || dst->n_kv_heads != src->n_kv_heads || dst->head_dim != src->head_dim || n_rows < 1)
     return HIPPO_ERR_BAD_SHAPE;
+  if (2 * (long long)src->n_kv_heads > 65535) return HIPPO_ERR_BAD_SHAPE;   // (KV head, K or V) is grid y
   if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_codes) || !aligned16(v_codes) ||
       (reinterpret_cast<uintptr_t>(workspace) & 255u) || (reinterpret_cast<uintptr_t>(k_scale) & 3u) ||
       (reinterpret_cast<uintptr_t>(v_scale) & 3u))

@@ -17,25 +17,6 @@
 
 #include "common.h"
 
-// Phase timestamps for kernel tuning: compiled in only when HIPPO_TRACE is defined (never in the
-// shipped library).  Lane 0 of every wave stores the shader clock at numbered points.
-#ifdef HIPPO_TRACE
-__device__ long long* g_hippo_trace;
-#define HIPPO_TP_DECL long long tp_[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-#define HIPPO_TP(i_) tp_[i_] = (long long)__builtin_readcyclecounter();
-#define HIPPO_TP_FLUSH                                                                            \
-  if ((threadIdx.x & 63) == 0) {                                                                  \
-    long long* dst_ = g_hippo_trace +                                                             \
-        ((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * (blockDim.x >> 6) + \
-         (threadIdx.x >> 6)) * 16;                                                                \
-    for (int q_ = 0; q_ < 9; ++q_) dst_[q_] = tp_[q_];                                            \
-  }
-#else
-#define HIPPO_TP_DECL
-#define HIPPO_TP(i_)
-#define HIPPO_TP_FLUSH
-#endif
-
 namespace hippo {
 
 // =================================================================================================
@@ -223,7 +204,12 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
   // the address is wave-uniform by construction; readfirstlane tells the compiler so where its own
   // analysis cannot (it must end up in a scalar register to reach M0)
   const unsigned uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform_addr)
+  // M0 carries the LDS address; the statement puts back what M0 held before, so the compiler's own
+  // uses of M0 (which an asm statement cannot declare as overwritten) are never disturbed
+  unsigned saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
+               : "v"(gptr), "s"(uniform_addr)
                : "memory");
 }
 template <int N>
@@ -426,9 +412,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       dma16(src + ((ld_pc ^ tile_swizzle<D, KV8>(r)) * 16), dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
     }
   };
-
-  HIPPO_TP_DECL
-  HIPPO_TP(0)
   // ---- prologue: the first ring stage goes out before anything else (its bytes are the ones
   // the first products wait for), then the query block, then the remaining stages.  Transfers
   // complete in issue order, so the wait for super-tile 0 below also covers the query block. ----
@@ -495,8 +478,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   const float scale_log2 = KV8 ? p.scale_log2 * k_mult : p.scale_log2;
 
   bf16x8 qop[KS];
-  int trace_it = 0;
-  (void)trace_it;
 
   for (int si = 0; si < n_super; ++si) {
     // Transfers complete in issue order, so "at most PER * (super-tiles requested after si)
@@ -505,7 +486,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     if (issuer) WaitLadder<NST - 1>::template run<PER>(issued - 1 - si); else wait_vmcnt<0>();
     __syncthreads();           // super-tile si complete in LDS; everyone is past super-tile si-1
     if (si == 0) {
-      HIPPO_TP(1)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
         qop[ks] = *(const bf16x8*)(Qs + rb * 16 * QROWB + j * QROWB +
@@ -521,7 +501,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     const unsigned char* Kt = ring + (si % NST) * SM::kSuperBytes + tg * 2 * SM::kTileBytes;
     const unsigned char* Vt = Kt + SM::kTileBytes;
     const int n0 = (t_lo + ti) * TT;
-    if (trace_it == 0) { HIPPO_TP(2) }
 
     f32x4 s[TB];
 #pragma unroll
@@ -544,7 +523,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
           s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(kraw[2], kraw[3]), qop[2 * c + 1], s[tb], 0, 0, 0);
         }
     }
-    if (trace_it == 0) { HIPPO_TP(3) }
 
     if ((n0 + TT - 1) > p.ctx_len) {                     // tile touches the causal edge
 #pragma unroll
@@ -582,7 +560,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       psum += __uint_as_float(pk[h] << 16) + __uint_as_float(pk[h] & 0xffff0000u);
     }
     l_run += psum;                                         // per-lane share; groups g meet at the end
-    if (trace_it == 0) { HIPPO_TP(4) }
 
     if (TB == 2) {
       const bf16x8 pop = __builtin_bit_cast(bf16x8, (i32x4_t){(int)pk[0], (int)pk[1], (int)pk[2 % (TB * 2)], (int)pk[3 % (TB * 2)]});
@@ -610,11 +587,8 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
         acc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop, pop, acc[db], 0, 0, 0);
       }
     }
-    if (trace_it == 0) { HIPPO_TP(5) }
-    ++trace_it;
   }
   wait_vmcnt<0>();   // no transfer may still be writing LDS past this point
-  HIPPO_TP(6)
 
   // ---- merge the TG token groups of every row block ----
   l_run = rows4_sum(l_run);
@@ -624,7 +598,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   }
   f32x4* xbuf = (f32x4*)ring;                              // [WAVES][DB][64 lanes]
   __syncthreads();   // (a) every wave is done reading the ring before anyone overwrites it
-  HIPPO_TP(7)
   // a wave finishes head-dim blocks tg, tg + TG, ...: those stay in its registers, only the blocks
   // that other waves finish go through LDS.  The body is instantiated once per value of tg (it is
   // wave-uniform), so which blocks stay and which travel is known at compile time: straight-line
@@ -676,8 +649,6 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   else if (tg == 1) finish(std::integral_constant<int, 1>());
   else if (tg == 2) finish(std::integral_constant<int, 2 % TG>());
   else finish(std::integral_constant<int, 3 % TG>());
-  HIPPO_TP(8)
-  HIPPO_TP_FLUSH
   if (APPEND && split == 0 && chunk == 0) append_new_rows<uint16_t, D>(p, b, hk);
 }
 
@@ -821,15 +792,7 @@ static hipError_t launch_grid(const AttnParams& p, hipStream_t st) {
 template <int D, int RB>
 static hipError_t launch_grid_rb(const AttnParams& p, hipStream_t st) {
   const int tiles32_per_block = ((p.n_total + 31) / 32) / (p.S > 0 ? p.S : 1);
-  const bool small_tiles = p.variant == 1 || (p.variant != 2 && tiles32_per_block < 24);
-#ifdef HIPPO_TUNE
-  if (p.variant == 10) return launch_grid<D, RB, 2, 16, 3>(p, st);
-  if (p.variant == 11) return launch_grid<D, RB, 4, 16, 3>(p, st);
-  if (p.variant == 12) return launch_grid<D, RB, 4, 16, 4>(p, st);
-  if (p.variant == 13) return launch_grid<D, RB, 2, 32, 2>(p, st);
-  if (p.variant == 14) return launch_grid<D, RB, 2, 32, 3>(p, st);
-  if (p.variant == 15) return launch_grid<D, RB, 4, 16, 2>(p, st);
-#endif
+  const bool small_tiles = tiles32_per_block < 24;
   if (!small_tiles) return launch_grid<D, RB, 4, 32, 2>(p, st);
   // measured at the 16K configuration: with 3-4 row blocks, two token groups and a four-stage ring
   // (the whole slice in flight at once) beat four groups by ~8 %; the block merge moves half the data
@@ -842,14 +805,7 @@ static hipError_t launch_grid_rb(const AttnParams& p, hipStream_t st) {
 template <int D, int RB>
 static hipError_t launch_kv8_rb(const AttnParams& p, hipStream_t st) {
   const int tiles32_per_block = ((p.n_total + 31) / 32) / (p.S > 0 ? p.S : 1);
-#ifdef HIPPO_TUNE
-  if (p.variant == 20) return launch_grid_mode<D, RB, 2, 32, 4, 0, true>(p, st);
-  if (p.variant == 21) return launch_grid_mode<D, RB, 4, 32, 2, 0, true>(p, st);
-  if (p.variant == 22) return launch_grid_mode<D, RB, 4, 32, 3, 0, true>(p, st);
-  if (p.variant == 23) return launch_grid_mode<D, RB, 2, 32, 2, 0, true>(p, st);
-  if (p.variant == 24) return launch_grid_mode<D, RB, 2, 32, 3, 0, true>(p, st);
-#endif
-  if (p.variant == 1 || (p.variant != 2 && tiles32_per_block < 24))
+  if (tiles32_per_block < 24)
     return launch_grid_mode<D, RB, 2, 32, 4, 0, true>(p, st);
   return launch_grid_mode<D, RB, 4, 32, 2, 0, true>(p, st);
 }

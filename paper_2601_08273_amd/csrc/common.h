@@ -115,7 +115,6 @@ struct AttnParams {
   int S;                  // number of KV splits
   int row_chunk;          // query rows handled by one block
   int n_chunks;           // ceil(R / row_chunk)
-  int variant;            // tile-size override for tuning runs: 0 = heuristic, 1 = 16-token, 2 = 32-token
   int wave_prio;          // 1: the partial kernel's waves raise their issue priority (verification is
                           // the critical path of a decoding round; the draft call runs beside it)
   // appended-row fusion: when k_new is set, cache rows ctx_len .. ctx_len+q_len-1 are taken from

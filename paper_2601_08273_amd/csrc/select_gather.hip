@@ -8,22 +8,6 @@
 // variation.
 #include "common.h"
 
-// Phase timestamps for tuning runs only (-DHIPPO_TRACE): thread 0 of block 0 records the cycle
-// counter at a few points and stores them at the end; compiled out of the library.
-#ifdef HIPPO_TRACE
-__device__ long long g_topk_trace[16];
-#define TOPK_TP_DECL long long tp_[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#define TOPK_TP(i_) tp_[i_] = (long long)wall_clock64();
-#define TOPK_TP_FLUSH                                              \
-  if (threadIdx.x == 0 && blockIdx.x == 0) {                       \
-    for (int i_ = 0; i_ < 10; ++i_) g_topk_trace[i_] = tp_[i_];    \
-  }
-#else
-#define TOPK_TP_DECL
-#define TOPK_TP(i_)
-#define TOPK_TP_FLUSH
-#endif
-
 namespace hippo {
 
 constexpr int kSelThreads = 1024;
@@ -107,9 +91,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   const float* sc = p.scores + (long long)b * p.Nv;
   int32_t* out = p.idx_out + (long long)b * p.k;
   const int n_chunks = (p.Nv + kSelThreads - 1) / kSelThreads;
-
-  TOPK_TP_DECL
-  TOPK_TP(0)
   // CACHED: thread t owns the NC consecutive scores t*NC .. t*NC+NC-1 (index order = thread order,
   // which makes the compaction a per-thread count plus one scan); 16-byte loads where the row allows
   unsigned keys[CACHED ? NC : 1];
@@ -133,8 +114,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   auto key_at = [&](int c) -> unsigned {     // NC = 0: key of chunk c for this thread (index must be < Nv)
     return score_key(sc[c * kSelThreads + tid]);
   };
-
-  TOPK_TP(1)
   // ---- radix select of the k-th largest key ----
   unsigned prefix = 0, need = (unsigned)p.k;   // `need` keys still wanted among those matching prefix
   const int shifts[3] = {20, 8, 0};
@@ -201,7 +180,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     __syncthreads();
     prefix = sh_prefix;
     need = sh_need;
-    TOPK_TP(2 + pass)
   }
   const unsigned thr = prefix;      // the k-th largest key
   const unsigned need_eq = need;    // how many keys equal to it are kept (lowest indices first)
@@ -236,7 +214,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     }
     if (lane == 63) wave_tot[0][wave] = incl;
     __syncthreads();
-    TOPK_TP(5)
     unsigned tot[kSelWaves];
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) tot[w] = wave_tot[0][w];
@@ -244,7 +221,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) before += (w < wave) ? tot[w] : 0u;
     unsigned gt_before = before >> 16, eq_before = before & 0xffffu;
-    TOPK_TP(6)
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       if (first + c < p.Nv) {
@@ -279,8 +255,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
       __syncthreads();
     }
   }
-  TOPK_TP(7)
-  TOPK_TP_FLUSH
 }
 
 // dst row n of (b, hk): n < vis_off -> src n ; n < vis_off + k -> src vis_off + idx[n - vis_off] ;

@@ -76,15 +76,23 @@ int hippo_vpsd_plan(const hippo_vpsd_state* s, hippo_vpsd_round* r) {
 
 int hippo_vpsd_commit(hippo_vpsd_state* s, const hippo_vpsd_round* r, int32_t n_accept, int32_t n_drafted_parallel) {
   if (s == nullptr || r == nullptr) return HIPPO_ERR_NULL_ARG;
-  if (r->mode != s->mode || n_accept < 0 || n_accept > r->verify_len || n_drafted_parallel < 0 ||
-      n_drafted_parallel > r->draft_parallel)
+  // every check comes before the first change of the state: a refused commit leaves it as it was.
+  // The round must be the one hippo_vpsd_plan derives from this state, field by field.
+  hippo_vpsd_round planned;
+  const int rc = hippo_vpsd_plan(s, &planned);
+  if (rc != HIPPO_OK) return rc;
+  if (r->mode != planned.mode || r->draft_serial != planned.draft_serial || r->verify_len != planned.verify_len ||
+      r->draft_parallel != planned.draft_parallel)
     return HIPPO_ERR_BAD_SHAPE;
+  if (n_accept < 0 || n_accept > r->verify_len || n_drafted_parallel < 0 || n_drafted_parallel > r->draft_parallel)
+    return HIPPO_ERR_BAD_SHAPE;
+  const bool all_accepted = n_accept == r->verify_len;
+  if (all_accepted && n_drafted_parallel != r->draft_parallel) return HIPPO_ERR_BAD_SHAPE;   // a kept batch must be whole
   s->n_rounds += 1;
   s->n_target_calls += 1;
   s->n_draft_tokens += r->draft_serial + n_drafted_parallel;
-  if (n_accept == r->verify_len) {
+  if (all_accepted) {
     // everything verified was right: the tokens drafted meanwhile become the next buffer
-    if (n_drafted_parallel != r->draft_parallel) return HIPPO_ERR_BAD_SHAPE;   // a kept batch must be whole
     s->n_emitted += n_accept;
     s->n_pending = r->draft_parallel;
     if (s->n_pending > 0) count_switch(s, HIPPO_VPSD_OPTIMISTIC);

@@ -1,4 +1,5 @@
-"""Helpers shared by the GPU parity tests: host<->device marshalling and the tolerances.
+"""Helpers shared by the GPU parity tests, the smoke run and the benchmark: host<->device marshalling
+and the tolerances.  No arithmetic of the method lives here.
 
 Tolerances (stated by the benchmark definition, with the reading used for values that cross zero):
   fp32 : |x - ref| <= 1e-5 * max(|ref|, rms(ref))

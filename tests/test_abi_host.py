@@ -124,6 +124,9 @@ def test_score_argument_errors(lib):
     assert _score(lib, kv, vid, emb=FAKE, emb_dim=512, emb_stride=516) == h.ERR_BAD_ALIGN
     assert _score(lib, kv, vid, emb=FAKE + 2, emb_dim=512, emb_stride=512) == h.ERR_BAD_ALIGN
     assert _score(lib, kv, vid, ws_bytes=4096) == h.ERR_WORKSPACE_TOO_SMALL
+    # shapes no kernel grid can hold are refused before the first launch: frames are a y dimension
+    assert _score(lib, kv, h.video_desc(65536, 2, 2, 128), seq_len=1 << 20) == h.ERR_BAD_SHAPE
+    assert _score(lib, kv, h.video_desc(65535, 2, 2, 128), seq_len=1 << 20, ws_bytes=4096) == h.ERR_WORKSPACE_TOO_SMALL
 
 
 def test_select_argument_errors(lib):
@@ -253,6 +256,9 @@ def test_quantize_argument_errors(lib):
     assert call(kc=FAKE + 4) == h.ERR_BAD_ALIGN
     assert call(d=_kv(dtype=h.DTYPE_FP8_E4M3, stride_n=128 + 8)) == h.ERR_BAD_ALIGN
     assert call(ws_bytes=need - 1) == h.ERR_WORKSPACE_TOO_SMALL
+    # (KV head, K or V) pairs are a y dimension of the launch: more than 32767 KV heads cannot be launched
+    many = dict(n_kv_heads=32768, n_q_heads=32768)
+    assert call(s=_kv(**many), d=_kv(dtype=h.DTYPE_FP8_E4M3, **many), ws_bytes=1 << 40) == h.ERR_BAD_SHAPE
 
 
 def test_attention_paged_argument_errors(lib):

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from gpu_util import assert_close, dev, host, prep
+from parity_util import assert_close, dev, host, prep
 
 pytestmark = pytest.mark.gpu
 

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from gpu_util import assert_close, assert_indices_consistent, dev, host, prep
+from parity_util import assert_close, assert_indices_consistent, dev, host, prep
 
 pytestmark = pytest.mark.gpu
 

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from gpu_util import assert_close, dev, host
+from parity_util import assert_close, dev, host
 
 pytestmark = pytest.mark.gpu
 

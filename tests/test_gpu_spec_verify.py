@@ -20,7 +20,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from gpu_util import dev, host, prep
+from parity_util import dev, host, prep
 
 pytestmark = pytest.mark.gpu
 

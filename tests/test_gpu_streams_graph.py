@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from gpu_util import assert_close, dev, host
+from parity_util import assert_close, dev, host
 
 pytestmark = pytest.mark.gpu
 
@@ -71,3 +71,33 @@ def test_two_stream_round_eager_and_graph(hippo):
         assert_close(host(out_d), rd, dt, "replay %d draft" % rep)
         if rep in (0, 3):
             assert torch.equal(out_v, eager_v) and torch.equal(out_d, eager_d)
+
+
+def test_two_non_default_streams_with_wrapper_allocated_buffers(hippo):
+    """Verify and draft on two side streams while the binding allocates workspace, outputs and lse
+    itself: those buffers must belong to the stream the kernels run on, or the allocator may hand
+    them to the allocations made here, between the calls, while the kernels still use them."""
+    cfg = si.CONFIGS["draft"]
+    x = si.make_inputs(cfg, 3)
+    dt, n = cfg.dtype, cfg.ctx_len
+    k, v = dev(x["k"], dt), dev(x["v"], dt)
+    q, q1 = dev(x["q_new"], dt), dev(x["q_new"][:, :1], dt)
+    rv, rlv = oracle.attention(x["q_new"], x["k"], x["v"], n)
+    rd, rld = oracle.attention(x["q_new"][:, :1], x["k"][:, :, :n + 1], x["v"][:, :, :n + 1], n)
+    sA, sB = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(6):
+        outs = []
+        for _ in range(4):                      # several calls in flight per stream, no workspace passed
+            ov = hippo.hippo_verify_attention(q, k, v, n, want_lse=True, stream=sA)
+            # allocations on the current (default) stream between the calls: what a recycled block would go to
+            junk = [torch.full((1 << 18,), float(rep), device="cuda") for _ in range(8)]
+            od = hippo.hippo_draft_attention(q1, k[:, :, :n + 1], v[:, :, :n + 1], n, want_lse=True, stream=sB)
+            outs.append((ov, od))
+            del junk
+        torch.cuda.synchronize()
+        for (ov, lv), (od, ld) in outs:
+            assert_close(host(ov), rv, dt, "verify on a side stream, rep %d" % rep)
+            assert_close(host(od), rd, dt, "draft on a side stream, rep %d" % rep)
+            np.testing.assert_allclose(host(lv), rlv, rtol=2.0 ** -9, atol=2.0 ** -9)
+            np.testing.assert_allclose(host(ld), rld, rtol=2.0 ** -9, atol=2.0 ** -9)

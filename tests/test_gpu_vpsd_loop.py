@@ -14,7 +14,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from gpu_util import assert_close, dev, host, prep
+from parity_util import assert_close, dev, host, prep
 from oracle import vpsd_ref
 
 pytestmark = pytest.mark.gpu

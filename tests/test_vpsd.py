@@ -155,8 +155,31 @@ def test_state_machine_errors():
     assert lib.hippo_vpsd_commit(C.byref(s), C.byref(r), 1, 2) == h.ERR_BAD_SHAPE      # kept batch incomplete
     stale = h.VpsdRound(h.VPSD_OPTIMISTIC, 0, 5, 5)
     assert lib.hippo_vpsd_commit(C.byref(s), C.byref(stale), 5, 5) == h.ERR_BAD_SHAPE  # not this state's round
+    # a round of the right mode whose other fields differ from the planned one is refused too
+    for bad in (h.VpsdRound(r.mode, r.draft_serial + 1, r.verify_len, r.draft_parallel),
+                h.VpsdRound(r.mode, r.draft_serial, r.verify_len + 1, r.draft_parallel),
+                h.VpsdRound(r.mode, r.draft_serial, r.verify_len, r.draft_parallel + 1)):
+        assert lib.hippo_vpsd_commit(C.byref(s), C.byref(bad), 0, 0) == h.ERR_BAD_SHAPE
     res = h.VpsdResult()
     assert lib.hippo_vpsd_simulate(7, 3, 1.0, 3.0, 0, None, 0, 10, C.byref(res)) == h.ERR_BAD_SHAPE
     assert lib.hippo_vpsd_simulate(2, 3, 0.0, 3.0, 0, None, 0, 10, C.byref(res)) == h.ERR_BAD_SHAPE
     assert lib.hippo_vpsd_simulate(2, 3, 1.0, 3.0, 0, None, 5, 10, C.byref(res)) == h.ERR_NULL_ARG
     assert lib.hippo_vpsd_simulate(2, 3, 1.0, 3.0, 0, None, 0, 10, None) == h.ERR_NULL_ARG
+
+
+def test_refused_commit_leaves_the_state_unchanged():
+    lib = h.load()
+    for gamma, buf in ((5, 0), (5, 12), (1, 0)):
+        s = h.vpsd_init(gamma, buf)
+        r = h.vpsd_plan(s)
+        before = bytes(s)
+        refused = [(r, r.verify_len + 1, r.draft_parallel), (r, -1, 0), (r, r.verify_len, r.draft_parallel + 1),
+                   (h.VpsdRound(1 - r.mode, r.draft_serial, r.verify_len, r.draft_parallel), 0, 0),
+                   (h.VpsdRound(r.mode, r.draft_serial, r.verify_len + 2, r.draft_parallel), 0, 0)]
+        if r.draft_parallel > 0:
+            refused.append((r, r.verify_len, r.draft_parallel - 1))     # fully accepted, kept batch incomplete
+        for rnd, n_acc, n_par in refused:
+            assert lib.hippo_vpsd_commit(C.byref(s), C.byref(rnd), n_acc, n_par) == h.ERR_BAD_SHAPE
+            assert bytes(s) == before, (gamma, buf, n_acc, n_par)
+        h.vpsd_commit(s, r, r.verify_len)                               # and the planned round still commits
+        assert s.n_rounds == 1
