@@ -48,7 +48,9 @@ enum hippo_status {
   HIPPO_ERR_BAD_DTYPE = 3,           /* dtype is not one the call supports */
   HIPPO_ERR_BAD_ALIGN = 4,           /* a pointer or stride breaks the 16-byte rule */
   HIPPO_ERR_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes below hippo_workspace_bytes(...) */
-  HIPPO_ERR_HIP = 6                  /* a HIP runtime call (launch) failed */
+  HIPPO_ERR_HIP = 6,                 /* a HIP runtime call (launch) failed */
+  HIPPO_ERR_STATIC_SCRATCH_LIMIT = 7 /* hippo_verify_attention_static: the shapes need more scratch
+                                        than hippo_static_scratch_bytes() */
 };
 
 enum hippo_dtype {
@@ -214,6 +216,27 @@ int hippo_draft_attention(const void* q, int32_t q_len,
                           int32_t ctx_len, float softmax_scale, int32_t num_splits,
                           void* out, float* lse_out,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * hippo_verify_attention for callers that can neither allocate device memory nor pass a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, result and errors as hippo_verify_attention minus the workspace pair; the split partials
+ * live in an array that is part of the library's device image (hippo_static_scratch_bytes() = 8 MiB on
+ * every GPU the library is used on, held until the process ends).  The call allocates and frees
+ * nothing.  Shapes whose partials exceed the array (hippo_workspace_bytes(HIPPO_CALL_VERIFY_ATTENTION,
+ * ...) > hippo_static_scratch_bytes(), e.g. many sequences with num_splits forced high) are refused
+ * with HIPPO_ERR_STATIC_SCRATCH_LIMIT before anything is enqueued.  Every call on a GPU uses that
+ * GPU's one array: calls must not overlap in time on one GPU (same stream, or ordered by events), or
+ * they race.  Nothing in the array has to be cleared between calls, whatever the previous call left.
+ * The array's device address is looked up on the first call on each device; hippo_static_scratch_init()
+ * does that lookup for the current device ahead of time (call it before capturing a graph).
+ */
+size_t hippo_static_scratch_bytes(void);
+int hippo_static_scratch_init(void);
+int hippo_verify_attention_static(const void* q, int32_t q_len,
+                                  const void* k_cache, const void* v_cache, const hippo_kv_desc* kv,
+                                  int32_t ctx_len, float softmax_scale, int32_t num_splits,
+                                  void* out, float* lse_out, void* stream);
 
 /*
  * The same two attention calls with the append of the new rows folded in (a cache-format variant for

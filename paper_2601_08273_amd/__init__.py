@@ -17,11 +17,13 @@ LIB_PATH = os.path.join(_HERE, "libhippo.so")
 DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3 = 0, 1, 2
 CALL_SCORE_TOKENS, CALL_SELECT_GATHER_KV, CALL_DRAFT_ATTENTION, CALL_VERIFY_ATTENTION = 0, 1, 2, 3
 SCORE_ATTN, SCORE_TEMP, SCORE_SPA, SCORE_ALL, SCORE_ACCUMULATE_ONLY = 1, 2, 4, 7, 8
-OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = range(7)
+(OK, ERR_NULL_ARG, ERR_BAD_SHAPE, ERR_BAD_DTYPE, ERR_BAD_ALIGN, ERR_WORKSPACE_TOO_SMALL, ERR_HIP,
+ ERR_STATIC_SCRATCH_LIMIT) = range(8)
 
 EXPORTS = ("hippo_status_string", "hippo_workspace_bytes", "hippo_score_tokens",
            "hippo_score_layers_workspace_bytes", "hippo_score_tokens_layers",
            "hippo_select_gather_kv", "hippo_verify_attention", "hippo_draft_attention",
+           "hippo_static_scratch_bytes", "hippo_static_scratch_init", "hippo_verify_attention_static",
            "hippo_verify_attention_append", "hippo_draft_attention_append",
            "hippo_verify_attention_paged", "hippo_draft_attention_paged",
            "hippo_verify_attention_fp8kv", "hippo_draft_attention_fp8kv",
@@ -103,6 +105,12 @@ def load():
     for fn in (lib.hippo_verify_attention, lib.hippo_draft_attention):
         fn.argtypes = [vp, i32, vp, vp, kvp, i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
+    lib.hippo_static_scratch_bytes.argtypes = []
+    lib.hippo_static_scratch_bytes.restype = sz
+    lib.hippo_static_scratch_init.argtypes = []
+    lib.hippo_static_scratch_init.restype = C.c_int
+    lib.hippo_verify_attention_static.argtypes = [vp, i32, vp, vp, kvp, i32, f32, i32, vp, vp, vp]
+    lib.hippo_verify_attention_static.restype = C.c_int
     for fn in (lib.hippo_verify_attention_paged, lib.hippo_draft_attention_paged):
         fn.argtypes = [vp, i32, vp, vp, vp, C.POINTER(PagedKvDesc), i32, f32, i32, vp, vp, vp, sz, vp]
         fn.restype = C.c_int
@@ -359,6 +367,27 @@ def hippo_draft_attention(q, k_cache, v_cache, ctx_len: int, softmax_scale: floa
                           want_lse: bool = False, out=None, workspace=None, stream=None, k_new=None, v_new=None):
     return _attention("hippo_draft_attention", CALL_DRAFT_ATTENTION, q, k_cache, v_cache, ctx_len,
                       softmax_scale, num_splits, want_lse, out, workspace, stream, k_new, v_new)
+
+
+@_allocates_on_its_stream
+def hippo_verify_attention_static(q, k_cache, v_cache, ctx_len: int, softmax_scale: float = 0.0, num_splits: int = 0,
+                                  lse_out=None, out=None, stream=None):
+    """hippo_verify_attention without a workspace: the split partials live in the library's own static
+    device array (calls on one GPU must not overlap).  Pass `out` (and `lse_out`) to keep the whole call
+    free of allocations."""
+    torch = _torch()
+    lib = load()
+    assert q.is_contiguous() and q.dim() == 4
+    B, q_len, H, d = q.shape
+    kv = kv_desc(k_cache, H)
+    assert v_cache.stride() == k_cache.stride() and v_cache.shape == k_cache.shape
+    if out is None:
+        out = torch.empty_like(q)
+    st = lib.hippo_verify_attention_static(_ptr(q), q_len, _ptr(k_cache), _ptr(v_cache), C.byref(kv), ctx_len,
+                                           float(softmax_scale or 0.0), num_splits, _ptr(out), _ptr(lse_out),
+                                           _stream(stream))
+    _check(st, "hippo_verify_attention_static")
+    return out
 
 
 @_allocates_on_its_stream

@@ -3,6 +3,8 @@
 // enqueued.
 #include <math.h>
 
+#include <atomic>
+
 #include "common.h"
 
 using namespace hippo;
@@ -219,6 +221,40 @@ int plan_spec(int batch, int gamma, int vocab, int dtype, SpecPlan* pl) {
 
 }  // namespace
 
+// ---- scratch for callers that cannot allocate -----------------------------------------------------
+// One array per GPU, part of the loaded code object: it exists from the moment the library is loaded on
+// a device until the process ends.  In host code the name `scratch` is only a handle for the runtime's
+// symbol lookup, never an address a kernel could use; the per-device address comes from
+// hipGetSymbolAddress and is what every launch receives.
+constexpr size_t kStaticScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // zero-initialised: not looked up yet
+
+// address of the current device's copy of the array (looked up once per device), or null with *status set
+void* static_scratch(int* status) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *status = HIPPO_ERR_HIP;
+    return nullptr;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      *status = HIPPO_ERR_HIP;
+      return nullptr;
+    }
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // every thread finds the same address
+  }
+  *status = HIPPO_OK;
+  return ptr;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* hippo_status_string(int status) {
@@ -230,6 +266,8 @@ const char* hippo_status_string(int status) {
     case HIPPO_ERR_BAD_ALIGN: return "pointer or stride is not 16-byte aligned (workspace: 256)";
     case HIPPO_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than hippo_workspace_bytes()";
     case HIPPO_ERR_HIP: return "HIP runtime error at kernel launch";
+    case HIPPO_ERR_STATIC_SCRATCH_LIMIT:
+      return "the call needs more scratch than the library's static array holds (hippo_static_scratch_bytes())";
     default: return "unknown status";
   }
 }
@@ -389,6 +427,34 @@ int hippo_draft_attention(const void* q, int32_t q_len, const void* k_cache, con
                           void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
   return attention_entry(HIPPO_CALL_DRAFT_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
                          num_splits, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+size_t hippo_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int hippo_static_scratch_init(void) {
+  int rc = HIPPO_OK;
+  static_scratch(&rc);
+  return rc;
+}
+
+int hippo_verify_attention_static(const void* q, int32_t q_len, const void* k_cache, const void* v_cache,
+                                  const hippo_kv_desc* kv, int32_t ctx_len, float softmax_scale,
+                                  int32_t num_splits, void* out, float* lse_out, void* stream) {
+  // every argument check that needs no device comes before the scratch lookup; the size check uses the
+  // same plan as the launch
+  if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr) return HIPPO_ERR_NULL_ARG;
+  int rc = check_kv(kv);
+  if (rc != HIPPO_OK) return rc;
+  if (ctx_len < 0 || q_len < 1 || (long long)ctx_len + q_len > 0x7fffff00ll) return HIPPO_ERR_BAD_SHAPE;
+  AttnPlan pl;
+  if ((rc = plan_attention(HIPPO_CALL_VERIFY_ATTENTION, kv, q_len, ctx_len + q_len, num_splits, &pl)) != HIPPO_OK)
+    return rc;
+  if (pl.bytes > kStaticScratchBytes) return HIPPO_ERR_STATIC_SCRATCH_LIMIT;
+  void* ws = static_scratch(&rc);
+  if (ws == nullptr) return rc;
+  // the split partials are written in full before the merge reads them: nothing has to start at zero
+  return attention_entry(HIPPO_CALL_VERIFY_ATTENTION, q, q_len, k_cache, v_cache, kv, ctx_len, softmax_scale,
+                         num_splits, out, lse_out, ws, kStaticScratchBytes, stream);
 }
 
 size_t hippo_spec_verify_workspace_bytes(int32_t batch, int32_t gamma, int32_t vocab, int32_t dtype) {

@@ -46,8 +46,8 @@ def test_struct_layout_matches_header():
 
 
 def test_status_strings(lib):
-    seen = {h.status_string(s) for s in range(7)}
-    assert len(seen) == 7 and h.status_string(0) == "ok"
+    seen = {h.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and h.status_string(0) == "ok"
     assert "unknown" in h.status_string(99)
 
 
@@ -85,6 +85,27 @@ def test_attention_argument_errors(lib):
     assert _verify(lib, _kv(stride_n=132)) == h.ERR_BAD_ALIGN          # 264-byte rows
     assert lib.hippo_verify_attention(FAKE, 6, FAKE, FAKE, None, 10, 0.0, 0, FAKE, None, FAKE, 1 << 20, None) \
         == h.ERR_NULL_ARG
+
+
+def test_static_scratch_argument_errors(lib):
+    """The entry point without a workspace: every refusal below happens before the device is touched."""
+    def call(kv, q_len=6, ctx=16640, q=FAKE, k=FAKE, v=FAKE, out=FAKE, splits=0):
+        return lib.hippo_verify_attention_static(q, q_len, k, v, C.byref(kv), ctx, 0.0, splits, out, None, None)
+    kv = _kv()
+    limit = lib.hippo_static_scratch_bytes()
+    assert limit == 8 << 20
+    assert call(kv, q=None) == h.ERR_NULL_ARG
+    assert call(kv, out=None) == h.ERR_NULL_ARG
+    assert call(kv, q_len=0) == h.ERR_BAD_SHAPE
+    assert call(kv, ctx=-1) == h.ERR_BAD_SHAPE
+    assert call(_kv(dtype=7)) == h.ERR_BAD_DTYPE
+    assert call(_kv(head_dim=96)) == h.ERR_BAD_SHAPE
+    # the headline shape fits; four sequences of eight KV heads with 64 forced slices do not
+    assert h.workspace_bytes(h.CALL_VERIFY_ATTENTION, kv, None, 6, 16646) <= limit
+    big = _kv(batch=4, n_q_heads=64, n_kv_heads=8)
+    assert h.workspace_bytes(h.CALL_VERIFY_ATTENTION, big, None, 6, 37126, 0, 64) > limit
+    assert call(big, ctx=37120, splits=64) == h.ERR_STATIC_SCRATCH_LIMIT
+    assert "static" in h.status_string(h.ERR_STATIC_SCRATCH_LIMIT)
 
 
 def test_workspace_query(lib):
