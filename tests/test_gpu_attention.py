@@ -64,6 +64,23 @@ def test_verify_random_shapes_sharp_softmax(hippo, dtype, shape):
         run_case(hippo, q, k, v, ctx, dtype, s, what="%s %s S=%d" % (dtype, shape, s))
 
 
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("shape", [
+    # q_len, G, ctx, forced slices: slices of at least 24 32-token tiles, the long-slice launch shape
+    (1, 7, 4096, 1),              # R = 7: one 16-row block (draft attention over an unpruned cache)
+    (1, 7, 4096, 2),
+    (5, 4, 2048, 1),              # R = 20: two row blocks
+    (9, 7, 3072, 2),              # R = 63: four row blocks
+    (3, 14, 1700, 1),             # R = 42: three row blocks, ragged last tile
+])
+def test_verify_long_slices_every_row_block_count(hippo, shape, d):
+    ql, G, ctx, S = shape
+    q, k, v = rand_case(ql * 1000 + G + d, 1, ql, 2 * G, 2, d, ctx, qscale=3.0 if d == 64 else 2.5)
+    run_case(hippo, q, k, v, ctx, "bf16", S, what="long slices %s d=%d" % (shape, d))
+    if ql == 1:
+        run_case(hippo, q, k, v, ctx, "bf16", S, fn="draft", what="long slices %s d=%d draft" % (shape, d))
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_causal_mask_probe_with_one_hot_values(hippo, dtype):
     # V = identity: the output IS the probability row.  Mass beyond ctx+i must be exactly zero.
@@ -143,15 +160,15 @@ def test_verify_full_size(hippo, name):
     run_case(hippo, x["q_new"], x["k"], x["v"], cfg.ctx_len, cfg.dtype, 0, what=name)
 
 
-def test_verify_full_size_large_share_sampled(hippo):
-    """Batch 4 x 8 KV heads x 37K rows: GPU runs everything, the oracle checks two batch elements."""
+def test_verify_full_size_large_share(hippo):
+    """Batch 4 x 8 KV heads x 37K rows, every batch element against the oracle."""
     cfg = si.CONFIGS["c5_large"]
     x = si.make_inputs(cfg, 0)
     dt = cfg.dtype
     out = hippo.hippo_verify_attention(dev(x["q_new"], dt), dev(x["k"], dt), dev(x["v"], dt), cfg.ctx_len)
     torch.cuda.synchronize()
     got = host(out)
-    for b in (0, 3):
+    for b in range(cfg.batch):
         ro, _ = oracle.attention(x["q_new"][b:b + 1], x["k"][b:b + 1], x["v"][b:b + 1], cfg.ctx_len)
         assert_close(got[b:b + 1], ro, dt, "c5 batch %d" % b)
 

@@ -59,6 +59,21 @@ def test_random_shapes_sharp_softmax(hippo, shape):
     run_case(hippo, q, k, v, ctx, 0, fn="draft", what="%s draft" % (shape,))
 
 
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("shape", [
+    # q_len, G, ctx, forced slices: slices of at least 24 32-token tiles (four token groups, two stages)
+    (1, 7, 4096, 1),              # R = 7: one 16-row block
+    (1, 7, 4096, 2),
+    (5, 4, 2048, 1),              # R = 20: two row blocks
+    (9, 7, 3072, 2),              # R = 63: four row blocks
+    (3, 14, 1700, 1),             # R = 42: three row blocks, ragged last tile
+])
+def test_long_slices_every_row_block_count(hippo, shape, d):
+    ql, G, ctx, S = shape
+    q, k, v = rand_case(ql * 1000 + G + d, 1, ql, 2 * G, 2, d, ctx, qscale=3.0 if d == 64 else 2.5)
+    run_case(hippo, q, k, v, ctx, S, what="fp8 long slices %s d=%d" % (shape, d))
+
+
 def test_causal_mask_probe_with_one_hot_values(hippo):
     # V = identity (code 0x38 = 1.0): the output IS the probability row; mass beyond ctx+i must be 0
     B, ql, H, Hkv, d, ctx = 1, 6, 4, 2, 128, 100

@@ -50,6 +50,10 @@ def test_score_on_configs(hippo, name):
     (2, 9, 8, 2, 128, 5, 16, 16, 6, 4, (5, 5)),    # 256-token frames: one token tile each
     (2, 6, 4, 2, 64, 3, 16, 32, 0, 1, (5, 5)),     # 512-token frames: two tiles per frame
     (1, 5, 4, 1, 64, 3, 32, 32, 2, 0, (4, 8)),     # 1024-token frames: four tiles, two values per thread
+    (1, 9, 4, 2, 64, 3, 13, 15, 3, 2, (6, 7)),     # 42-token crops (three 16-row blocks), ragged: 6+6+1 by 7+7+1
+    (2, 5, 8, 2, 128, 4, 12, 16, 0, 1, (6, 8)),    # 48-token crops tiling the grid exactly
+    (1, 6, 4, 1, 128, 2, 14, 17, 5, 0, (6, 8)),    # 48-token crops cut by both edges (2-row and 1-column rests)
+    (1, 4, 2, 1, 64, 3, 10, 14, 1, 1, (5, 7)),     # 35-token crops: barely past the two-block kernel
 ])
 def test_score_random_shapes(hippo, dtype, shape):
     B, L, H, Hkv, d, F, gh, gw, off, tail, (ch, cw) = shape
