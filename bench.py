@@ -419,10 +419,9 @@ def calibration(torch, np, capture, med, kv_bytes, L):
     half = [torch.randn(n_el // 2, device="cuda").to(torch.bfloat16) for _ in range(L)]
     dst = torch.empty(n_el // 2, dtype=torch.bfloat16, device="cuda")
     full = [torch.randn(n_el, device="cuda").to(torch.bfloat16) for _ in range(L)]
-    words = [x.view(torch.int32) for x in full]
     tiny = torch.zeros(64, device="cuda")
-    acc = torch.zeros(L, device="cuda")
-    flags = torch.zeros(L, dtype=torch.bool, device="cuda")
+    acc = list(torch.zeros(L, device="cuda").unbind(0))
+    top = list(torch.zeros(L, dtype=torch.bfloat16, device="cuda").unbind(0))
     mb = kv_bytes / 1e6
 
     def empty_chain():
@@ -435,15 +434,15 @@ def calibration(torch, np, capture, med, kv_bytes, L):
 
     def sum_chain():                                      # reads kv_bytes per call
         for l in range(L):
-            torch.sum(full[l], dtype=torch.float32, out=acc[l])
+            torch.sum(full[l], dim=0, dtype=torch.float32, out=acc[l])
 
-    def any_chain():                                      # reads kv_bytes per call, as 32-bit words
+    def amax_chain():                                     # reads kv_bytes per call
         for l in range(L):
-            torch.any(words[l], out=flags[l])
+            torch.amax(full[l], dim=0, out=top[l])
 
     out["calib:launch_that_does_nothing(chain of %d)" % (2 * L)] = round(med(capture(empty_chain), per=2 * L), 3)
     out["calib:copy(%.1f MB in, %.1f MB out)" % (mb / 2, mb / 2)] = round(med(capture(copy_chain), per=L), 3)
-    for name, fn in (("calib:sum(%.1f MB read)" % mb, sum_chain), ("calib:any(%.1f MB read)" % mb, any_chain)):
+    for name, fn in (("calib:sum(%.1f MB read)" % mb, sum_chain), ("calib:amax(%.1f MB read)" % mb, amax_chain)):
         try:
             out[name] = round(med(capture(fn), per=L), 3)
         except Exception as exc:                          # a reduction the graph cannot hold: say so, go on

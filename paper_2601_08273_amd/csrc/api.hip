@@ -150,6 +150,7 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
   p.scale_log2 = scale * kLog2e;
   p.S = pl.S; p.row_chunk = pl.row_chunk; p.n_chunks = pl.n_chunks;
   p.wave_prio = call == HIPPO_CALL_VERIFY_ATTENTION ? 1 : 0;
+  p.phase_per_head = 1.0f / (float)((long long)kv->batch * kv->n_kv_heads);
   p.k_new = append ? k_new : nullptr; p.v_new = append ? v_new : nullptr;
   p.k_w = const_cast<void*>(k_cache); p.v_w = const_cast<void*>(v_cache);
   p.block_table = ex.block_table; p.page_shift = page_shift; p.max_pages = ex.max_pages;

@@ -200,6 +200,9 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 // 16 bytes per lane from global memory straight into LDS at lds_addr + lane*16 (lds_addr uniform).
 // Issued from inline assembly with hand-placed vmcnt waits: the compiler would otherwise wait for
 // every outstanding transfer before each LDS read.
+// NT marks the transfer non-temporal: the bytes are read once and must not displace what the caches
+// could still serve (used for caches far larger than the chip's last-level cache).
+template <bool NT = false>
 __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
   // the address is wave-uniform by construction; readfirstlane tells the compiler so where its own
   // analysis cannot (it must end up in a scalar register to reach M0)
@@ -207,10 +210,16 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
   // M0 carries the LDS address; the statement puts back what M0 held before, so the compiler's own
   // uses of M0 (which an asm statement cannot declare as overwritten) are never disturbed
   unsigned saved_m0;
-  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-               : "=&s"(saved_m0)
-               : "v"(gptr), "s"(uniform_addr)
-               : "memory");
+  if constexpr (NT)
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "v"(gptr), "s"(uniform_addr)
+                 : "memory");
+  else
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "v"(gptr), "s"(uniform_addr)
+                 : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -306,7 +315,7 @@ __device__ __forceinline__ bf16x8 e4m3x8_to_bf16(int lo, int hi) {
 
 // TT = tokens per tile (16 or 32), NST = ring stages (super-tiles resident in LDS)
 // MODE: 0 = contiguous cache, 1 = contiguous cache with appended-row fusion, 2 = paged cache
-template <int D, int RB, int TG, int TT, int NST, int MODE, bool KV8 = false>
+template <int D, int RB, int TG, int TT, int NST, int MODE, bool KV8 = false, bool NT = false, bool ROT = false>
 __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) {
   constexpr bool APPEND = MODE == 1, PAGED = MODE == 2;
   constexpr int ES = KV8 ? 1 : 2;                      // bytes per cache element
@@ -372,6 +381,21 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   const int t_hi = t_lo + tq + (split < tr ? 1 : 0);
   const int n_blk = t_hi - t_lo;                           // tiles of this block
   const int n_super = (n_blk + TG - 1) / TG;
+  // ROT (long slices): the softmax state does not care in which order a slice's tiles arrive, so every
+  // (batch element, KV head) starts its slices at a different phase and wraps around.  Blocks that
+  // would otherwise walk their slices in lockstep, a fixed stride apart, then spread over the memory
+  // channels (4 sequences x 8 KV heads x 37K rows in 8 slices: 10 % faster).  The phase is this head's
+  // share of the slice, in single precision: any value in range serves, and an integer division here
+  // would sit in front of the block's first transfer.
+  int phase = 0;
+  if constexpr (ROT)
+    phase = __builtin_amdgcn_readfirstlane(   // wave-uniform: keep it in a scalar register
+        min((int)((float)(b * p.Hkv + hk) * (float)n_super * p.phase_per_head), max(n_super - 1, 0)));
+  auto super_at = [&](int si) {
+    if constexpr (!ROT) return si;
+    const int x = si + phase;
+    return x >= n_super ? x - n_super : x;
+  };
 
   // issuing wave w moves transfers x = w*PER .. w*PER+PER-1 of a super-tile:
   //   x -> tile tt = x / (2 NLD), K or V = (x / NLD) & 1, 1 KB piece n = x % NLD
@@ -394,7 +418,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   }
   auto issue_super = [&](int si) {
     const unsigned dst = ring_addr + (si % NST) * SM::kSuperBytes;
-    const int tile0 = t_lo + si * TG;
+    const int tile0 = t_lo + super_at(si) * TG;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
       const int x = wave * PER + u;
@@ -409,7 +433,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       if (APPEND && row >= p.ctx_len)                      // a row that has not reached the cache yet
         src = (const char*)(which ? p.v_new : p.k_new) +
               ((((long long)b * p.q_len + (row - p.ctx_len)) * p.Hkv + hk) * D) * 2;
-      dma16(src + ((ld_pc ^ tile_swizzle<D, KV8>(r)) * 16), dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
+      dma16<NT>(src + ((ld_pc ^ tile_swizzle<D, KV8>(r)) * 16), dst + (tt * 2 + which) * SM::kTileBytes + n * 1024);
     }
   };
   // ---- prologue: the first ring stage goes out before anything else (its bytes are the ones
@@ -495,7 +519,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       if (issuer) issue_super(issued);
       ++issued;
     }
-    const int ti = si * TG + tg;                           // this wave's tile inside the block
+    const int ti = super_at(si) * TG + tg;                 // this wave's tile inside the block
     if (ti >= n_blk) continue;                             // ragged last super-tile
 
     const unsigned char* Kt = ring + (si % NST) * SM::kSuperBytes + tg * 2 * SM::kTileBytes;
@@ -757,7 +781,7 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
 // =================================================================================================
 // host launch
 // =================================================================================================
-template <int D, int RB, int TG, int TT, int NST, int MODE, bool KV8 = false>
+template <int D, int RB, int TG, int TT, int NST, int MODE, bool KV8 = false, bool NT = false, bool ROT = false>
 static hipError_t launch_grid_mode(const AttnParams& p, hipStream_t st) {
   // the paged variant keeps its slice of the page table behind the ring
   constexpr int smem = GridSmem<D, TG, TT, NST, KV8 ? 1 : 2>::total(RB) + (MODE == 2 ? kMaxSlicePages * 4 : 0);
@@ -768,23 +792,31 @@ static hipError_t launch_grid_mode(const AttnParams& p, hipStream_t st) {
   if (e != hipSuccess) return e;
   const unsigned long long bit = 1ull << (dev & 63);
   if (!(attr_set.load(std::memory_order_acquire) & bit)) {
-    e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8>,
+    e = hipFuncSetAttribute((const void*)attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8, NT, ROT>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set.fetch_or(bit, std::memory_order_release);
   }
   dim3 grid(p.S, p.Hkv, p.B * p.n_chunks);
-  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8>), grid, dim3(RB * TG * 64), smem, st, p);
+  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8, NT, ROT>), grid, dim3(RB * TG * 64), smem, st, p);
   return hipGetLastError();
 }
 
 // the appended-row and paged variants are separate instantiations, so the plain call carries none of
 // their address selects
-template <int D, int RB, int TG, int TT, int NST>
+template <int D, int RB, int TG, int TT, int NST, bool NT = false, bool ROT = false>
 static hipError_t launch_grid(const AttnParams& p, hipStream_t st) {
-  if (p.block_table != nullptr) return launch_grid_mode<D, RB, TG, TT, NST, 2>(p, st);
-  if (p.k_new != nullptr) return launch_grid_mode<D, RB, TG, TT, NST, 1>(p, st);
-  return launch_grid_mode<D, RB, TG, TT, NST, 0>(p, st);
+  if (p.block_table != nullptr) return launch_grid_mode<D, RB, TG, TT, NST, 2, false, NT, ROT>(p, st);
+  if (p.k_new != nullptr) return launch_grid_mode<D, RB, TG, TT, NST, 1, false, NT, ROT>(p, st);
+  return launch_grid_mode<D, RB, TG, TT, NST, 0, false, NT, ROT>(p, st);
+}
+
+// A call whose K and V exceed the chip's last-level cache (256 MB) streams them with non-temporal
+// transfers: nothing of such a stream can be served from a cache again, and left to itself it evicts
+// the query block, the split partials and the other stream's data (measured on 4 sequences x 8 KV
+// heads x 37K rows, 608 MB: 6 % faster; at 34 MB the hint costs 5 %, so short streams do not use it).
+static bool stream_exceeds_caches(const AttnParams& p, int head_dim, int elem_bytes) {
+  return 2ll * p.B * p.Hkv * p.n_total * head_dim * elem_bytes > (256ll << 20);
 }
 
 // Short slices (a block owns only a handful of tiles, as at 16K context on 256 compute units) use
@@ -793,9 +825,14 @@ template <int D, int RB>
 static hipError_t launch_grid_rb(const AttnParams& p, hipStream_t st) {
   const int tiles32_per_block = ((p.n_total + 31) / 32) / (p.S > 0 ? p.S : 1);
   const bool small_tiles = tiles32_per_block < 24;
-  if (!small_tiles) return launch_grid<D, RB, 4, 32, 2>(p, st);
+  if (!small_tiles)
+    return stream_exceeds_caches(p, D, 2) ? launch_grid<D, RB, 4, 32, 2, true, true>(p, st)
+                                          : launch_grid<D, RB, 4, 32, 2, false, true>(p, st);
   // measured at the 16K configuration: with 3-4 row blocks, two token groups and a four-stage ring
   // (the whole slice in flight at once) beat four groups by ~8 %; the block merge moves half the data
+  // four row blocks (49-64 query rows) over slices of 12-23 32-token tiles, the 33K long-video shape:
+  // the per-tile work of the vector unit weighs most there, and 32-token tiles halve it per token
+  if (RB == 4 && tiles32_per_block >= 12) return launch_grid<D, RB, 2, 32, 3>(p, st);
   if (RB >= 3) return launch_grid<D, RB, 2, 16, 4>(p, st);
   return launch_grid<D, RB, 4, 16, 3>(p, st);
 }
@@ -807,7 +844,8 @@ static hipError_t launch_kv8_rb(const AttnParams& p, hipStream_t st) {
   const int tiles32_per_block = ((p.n_total + 31) / 32) / (p.S > 0 ? p.S : 1);
   if (tiles32_per_block < 24)
     return launch_grid_mode<D, RB, 2, 32, 4, 0, true>(p, st);
-  return launch_grid_mode<D, RB, 4, 32, 2, 0, true>(p, st);
+  if (stream_exceeds_caches(p, D, 1)) return launch_grid_mode<D, RB, 4, 32, 2, 0, true, true, true>(p, st);
+  return launch_grid_mode<D, RB, 4, 32, 2, 0, true, false, true>(p, st);
 }
 
 template <int D>

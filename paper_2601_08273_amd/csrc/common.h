@@ -115,6 +115,8 @@ struct AttnParams {
   int S;                  // number of KV splits
   int row_chunk;          // query rows handled by one block
   int n_chunks;           // ceil(R / row_chunk)
+  float phase_per_head;   // 1 / (B * Hkv): (batch element, KV head) number i starts its slices i * this of the
+                          // way in and wraps around; 0 = every slice is walked from its first tile
   int wave_prio;          // 1: the partial kernel's waves raise their issue priority (verification is
                           // the critical path of a decoding round; the draft call runs beside it)
   // appended-row fusion: when k_new is set, cache rows ctx_len .. ctx_len+q_len-1 are taken from

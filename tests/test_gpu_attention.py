@@ -189,6 +189,7 @@ def test_verify_full_size_large_share(hippo):
     (1, 12, 16, 2, 64, 515, 3),      # two row chunks
     (1, 40, 4, 2, 64, 24, 2),        # more new rows than context: they span both slices
     (1, 2, 6, 2, 64, 0, 0),          # empty context
+    (2, 4, 16, 4, 128, 1900, 2),     # long slices (rotated start): the new rows sit in the middle of the walk
 ])
 def test_append_fusion(hippo, dtype, fn, shape):
     B, ql, H, Hkv, d, ctx, ns = shape
@@ -273,6 +274,8 @@ def to_pages(x, page_size, n_pool, rng):
     (1, 12, 16, 2, 64, 515, 256, 3),      # pages larger than a slice
     (1, 6, 28, 4, 128, 5000, 16, 0),      # many small pages
     (1, 2, 6, 2, 64, 0, 16, 0),           # empty context
+    (2, 4, 16, 4, 128, 1900, 16, 2),      # long slices (rotated start) over small pages
+    (1, 3, 8, 4, 64, 3000, 128, 1),       # one long slice per KV head, each head at its own phase
 ])
 def test_paged_cache(hippo, dtype, shape):
     B, ql, H, Hkv, d, ctx, ps, ns = shape
