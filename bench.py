@@ -238,6 +238,21 @@ def main():
         us["alone:verify_per_layer"] = round(t_verify_alone, 3)
         us["alone:draft_per_layer"] = round(med(capture(draft_all), per=L), 3)
         us["alone:score_tokens"] = round(med(capture(score_only)), 2)
+        if dt == "bf16":
+            # the draft call again on the same values held as an fp32 cache: that cache type runs the
+            # vector-ALU split-KV kernel, the bf16 cache the MFMA kernel padded to one 16-row block
+            kp32, vp32 = [x.float() for x in kp], [x.float() for x in vp]
+            qdraft32 = [x.float() for x in qdraft]
+            out_dr32 = torch.empty_like(qdraft32[0])
+            ws_dr32 = torch.empty(h.workspace_bytes(h.CALL_DRAFT_ATTENTION, h.kv_desc(kp32[0], cfg.n_q_heads), None, 1,
+                                                    n_dctx + 1), dtype=torch.uint8, device="cuda")
+
+            def draft_fp32_all():
+                for l in range(L):
+                    h.hippo_draft_attention(qdraft32[l], kp32[l], vp32[l], n_dctx, out=out_dr32, workspace=ws_dr32)
+
+            us["alone:draft_per_layer(fp32 cache: vector-ALU kernel)"] = round(med(capture(draft_fp32_all), per=L), 3)
+            del kp32, vp32
         us["alone:prune"] = round(med(run_prune), 2)
 
         # appended-row fusion: the q_len new rows arrive as [B, q_len, Hkv, d] and reach the cache inside

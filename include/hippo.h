@@ -207,8 +207,10 @@ int hippo_verify_attention(const void* q, int32_t q_len,
 
 /*
  * Draft-decode attention over the pruned cache (Preliminaries, "Speculative Decoding": the draft
- * model is invoked gamma times, one new token per forward).  Same contract and arguments as
- * hippo_verify_attention; the launch heuristics assume q_len = 1 and a short cache.  Running it on
+ * model is invoked gamma times, one new token per forward).  Same contract, arguments, kernels and
+ * split heuristic as hippo_verify_attention (measured: the matrix-unit kernel padded to one 16-row
+ * block beats the vector-ALU kernel 4-9 x at G = 7 or 8 rows); the one difference is that its waves
+ * do not raise their issue priority, so a verification running beside it keeps the right of way.  Running it on
  * the cache hippo_select_gather_kv built with k = N_v equals attention over the unpruned cache.
  */
 int hippo_draft_attention(const void* q, int32_t q_len,

@@ -197,49 +197,6 @@ constexpr float kRescaleGap = 8.f;    // log2 units, see the lazy rescale in the
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-// 16 bytes per lane from global memory straight into LDS at lds_addr + lane*16 (lds_addr uniform).
-// Issued from inline assembly with hand-placed vmcnt waits: the compiler would otherwise wait for
-// every outstanding transfer before each LDS read.
-// NT marks the transfer non-temporal: the bytes are read once and must not displace what the caches
-// could still serve (used for caches far larger than the chip's last-level cache).
-template <bool NT = false>
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
-  // the address is wave-uniform by construction; readfirstlane tells the compiler so where its own
-  // analysis cannot (it must end up in a scalar register to reach M0)
-  const unsigned uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  // M0 carries the LDS address; the statement puts back what M0 held before, so the compiler's own
-  // uses of M0 (which an asm statement cannot declare as overwritten) are never disturbed
-  unsigned saved_m0;
-  if constexpr (NT)
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0)
-                 : "v"(gptr), "s"(uniform_addr)
-                 : "memory");
-  else
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0)
-                 : "v"(gptr), "s"(uniform_addr)
-                 : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-template <int N>
-struct WaitLadder {   // s_waitcnt vmcnt(step * later) for a run-time, wave-uniform `later` in [0, N]
-  template <int STEP>
-  static __device__ __forceinline__ void run(int later) {
-    if (later >= N) wait_vmcnt<(STEP * N > 63 ? 63 : STEP * N)>();
-    else WaitLadder<N - 1>::template run<STEP>(later);
-  }
-};
-template <>
-struct WaitLadder<0> {
-  template <int STEP>
-  static __device__ __forceinline__ void run(int) { wait_vmcnt<0>(); }
-};
-
 // =================================================================================================
 // MFMA partial kernel (bf16): query-row blocks x token groups
 // =================================================================================================
@@ -293,7 +250,7 @@ struct GridSmem {
 // lane j receives column j of the 8 rows) then fetches exactly those 8 tokens of V^T in one read.
 template <int D, bool KV8>
 __device__ __forceinline__ int tile_swizzle(int r) {
-  if constexpr (!KV8) return (r / (256 / (D * 2))) & (D / 8 - 1);
+  if constexpr (!KV8) return lds_row_swizzle<D>(r);
   // 128-byte rows: the K reads of 16 lanes touch rows {0-3, 8-11, 16-19, 24-27} (+4), the V reads of
   // 32 lanes 16 consecutive rows; both must spread over the 16 16-byte slots of 256 bytes
   else if constexpr (D == 128) return ((r >> 1) ^ ((r >> 3) & 2)) & 7;

@@ -95,6 +95,57 @@ __device__ __forceinline__ float rows4_sum(float v) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// ---- HBM -> LDS transfers without registers in between -------------------------------------------
+// 16 bytes per lane from global memory straight into LDS at lds_addr + lane*16 (lds_addr uniform).
+// Issued from inline assembly with hand-placed vmcnt waits: the compiler would otherwise wait for
+// every outstanding transfer before each LDS read.
+// NT marks the transfer non-temporal: the bytes are read once and must not displace what the caches
+// could still serve (used for caches far larger than the chip's last-level cache).
+template <bool NT = false>
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
+  // the address is wave-uniform by construction; readfirstlane tells the compiler so where its own
+  // analysis cannot (it must end up in a scalar register to reach M0)
+  const unsigned uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  // M0 carries the LDS address; the statement puts back what M0 held before, so the compiler's own
+  // uses of M0 (which an asm statement cannot declare as overwritten) are never disturbed
+  unsigned saved_m0;
+  if constexpr (NT)
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "v"(gptr), "s"(uniform_addr)
+                 : "memory");
+  else
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "v"(gptr), "s"(uniform_addr)
+                 : "memory");
+}
+// A tile that such transfers fill is row-major and unpadded (a lane's 16 bytes land at base + lane*16);
+// bank conflicts of the MFMA operand reads are avoided by fetching, for physical 16-byte chunk c of
+// tile row r, logical chunk c ^ lds_row_swizzle(r).  D = bf16 elements per row.
+template <int D>
+__device__ __forceinline__ int lds_row_swizzle(int r) { return (r / (256 / (D * 2))) & (D / 8 - 1); }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int N>
+struct WaitLadder {   // s_waitcnt vmcnt(step * later) for a run-time, wave-uniform `later` in [0, N]
+  template <int STEP>
+  static __device__ __forceinline__ void run(int later) {
+    if (later >= N) wait_vmcnt<(STEP * N > 63 ? 63 : STEP * N)>();
+    else WaitLadder<N - 1>::template run<STEP>(later);
+  }
+};
+template <>
+struct WaitLadder<0> {
+  template <int STEP>
+  static __device__ __forceinline__ void run(int) { wait_vmcnt<0>(); }
+};
+
+
 // ---- host side ---------------------------------------------------------------------------------
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
