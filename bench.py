@@ -367,6 +367,12 @@ def main():
         us["alone:spec_verify(greedy, V=%d)" % V] = round(med(capture(spec_greedy), per=SD_REPS), 2)
 
         us.update(calibration(torch, np, capture, med, kv_bytes, L))
+        if args.workload == "c3_16k":                      # the same copies at the other configurations' sizes
+            for name in ("c4_long", "c5_large"):
+                c = si.CONFIGS[name]
+                nbytes = c.batch * c.n_kv_heads * (c.ctx_len + c.q_len) * c.head_dim * 2 * 2
+                us.update(calibration(torch, np, capture, med, nbytes, max(2, min(28, int(2.5e9 // nbytes))),
+                                      copies_only=True))
 
         # ---- the other bandwidth-bound configurations, so that a default run records them too ----
         if args.workload == "c3_16k":
@@ -425,7 +431,7 @@ def main():
     print(json.dumps(result), flush=True)
 
 
-def calibration(torch, np, capture, med, kv_bytes, L):
+def calibration(torch, np, capture, med, kv_bytes, L, copies_only=False):
     """What this machine gives any kernel of the verify call's shape, measured with tensor-library
     kernels only: L dependent launches over L distinct buffers of one layer's K+V bytes each, replayed
     from the same kind of graph as the verify calls."""
@@ -433,19 +439,25 @@ def calibration(torch, np, capture, med, kv_bytes, L):
     n_el = kv_bytes // 2                                  # 16-bit elements in one layer's K+V
     half = [torch.randn(n_el // 2, device="cuda").to(torch.bfloat16) for _ in range(L)]
     dst = torch.empty(n_el // 2, dtype=torch.bfloat16, device="cuda")
-    full = [torch.randn(n_el, device="cuda").to(torch.bfloat16) for _ in range(L)]
-    tiny = torch.zeros(64, device="cuda")
-    acc = list(torch.zeros(L, device="cuda").unbind(0))
-    top = list(torch.zeros(L, dtype=torch.bfloat16, device="cuda").unbind(0))
     mb = kv_bytes / 1e6
-
-    def empty_chain():
-        for _ in range(2 * L):                            # as many launches as L verify calls make
-            tiny.add_(1.0)
 
     def copy_chain():                                     # reads kv_bytes / 2 and writes kv_bytes / 2 per launch
         for l in range(L):
             dst.copy_(half[l])
+
+    out["calib:copy(%.1f MB in, %.1f MB out)" % (mb / 2, mb / 2)] = round(med(capture(copy_chain), per=L), 3)
+    del half, dst
+    if copies_only:
+        torch.cuda.empty_cache()
+        return out
+    full = [torch.randn(n_el, device="cuda").to(torch.bfloat16) for _ in range(L)]
+    tiny = torch.zeros(64, device="cuda")
+    acc = list(torch.zeros(L, device="cuda").unbind(0))
+    top = list(torch.zeros(L, dtype=torch.bfloat16, device="cuda").unbind(0))
+
+    def empty_chain():
+        for _ in range(2 * L):                            # as many launches as L verify calls make
+            tiny.add_(1.0)
 
     def sum_chain():                                      # reads kv_bytes per call
         for l in range(L):
@@ -456,7 +468,6 @@ def calibration(torch, np, capture, med, kv_bytes, L):
             torch.amax(full[l], dim=0, out=top[l])
 
     out["calib:launch_that_does_nothing(chain of %d)" % (2 * L)] = round(med(capture(empty_chain), per=2 * L), 3)
-    out["calib:copy(%.1f MB in, %.1f MB out)" % (mb / 2, mb / 2)] = round(med(capture(copy_chain), per=L), 3)
     for name, fn in (("calib:sum(%.1f MB read)" % mb, sum_chain), ("calib:amax(%.1f MB read)" % mb, amax_chain)):
         try:
             out[name] = round(med(capture(fn), per=L), 3)
