@@ -191,6 +191,11 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
 // =================================================================================================
 // MFMA partial kernel (bf16): helpers
 // =================================================================================================
+// r / G for a query-row number r < 4096 and a group size G <= 4096 without an integer division (which
+// costs some forty instructions in front of a block's transfers): (r + 1/2) * (1/G) lies at least
+// 1/(2G) away from every integer, hundreds of times the rounding error of the two operations.
+__device__ __forceinline__ int row_div_group(int r, float inv_g) { return (int)(((float)r + 0.5f) * inv_g); }
+
 constexpr int kMfmaTile = 32;         // tokens per tile the host-side split heuristic counts in
 constexpr float kRescaleGap = 8.f;    // log2 units, see the lazy rescale in the kernel
 
@@ -310,8 +315,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   const int rb = wave % RB, tg = wave / RB;
   const int j = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, hk = blockIdx.y;
-  const int b = blockIdx.z / p.n_chunks, chunk = blockIdx.z % p.n_chunks;
+  // (the usual single row chunk needs no division: nothing that can be avoided stands in front of the
+  // block's first transfer)
+  const int b = p.n_chunks == 1 ? (int)blockIdx.z : (int)(blockIdx.z / p.n_chunks);
+  const int chunk = p.n_chunks == 1 ? 0 : (int)(blockIdx.z % p.n_chunks);
   const int r0 = chunk * (RB * 16);
+  const float inv_g = __builtin_amdgcn_rcpf((float)p.G);
 
   // fp8 cache: the K multiplier scales the logits, the V multiplier the slice's output.  Fetched
   // first, through the scalar cache (a vector load here would sit behind every K/V transfer in the
@@ -327,13 +336,12 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   // paged: the pools' base plus the head offset; the page and the row inside it are added per transfer
   const char* kbase = (const char*)p.k + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * ES;
   const char* vbase = (const char*)p.v + ((PAGED ? 0ll : (long long)b * p.sb) + (long long)hk * p.sh) * ES;
-  const long long row_bytes = p.sn * ES;
+  const unsigned row_bytes = (unsigned)(p.sn * ES);        // the host caps the row stride at 2^24 elements
   const int ld_row = lane / CPR, ld_pc = lane % CPR;
 
   // the tiles are dealt to the S slices as evenly as possible, the first n_tiles % S slices taking
   // one more (32-bit arithmetic: this runs before the first transfer can be issued)
-  const int n_tiles = (p.n_total + TT - 1) / TT;
-  const int tq = n_tiles / p.S, tr = n_tiles % p.S;
+  const int tq = p.tiles_q, tr = p.tiles_r;   // n_tiles / S and n_tiles % S for this kernel's tile size, from the host
   const int t_lo = split * tq + min(split, tr);
   const int t_hi = t_lo + tq + (split < tr ? 1 : 0);
   const int n_blk = t_hi - t_lo;                           // tiles of this block
@@ -358,14 +366,14 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   //   x -> tile tt = x / (2 NLD), K or V = (x / NLD) & 1, 1 KB piece n = x % NLD
   // tiles past the block's range and rows past the cache's end re-read the block's last valid row
   // (a cache hit), so every super-tile costs every issuer exactly PER transfers
-  const long long row_cap = ((long long)t_hi * TT < p.n_total ? (long long)t_hi * TT : p.n_total) - 1;
+  const int row_cap = min(t_hi * TT, p.n_total) - 1;       // 32-bit row numbers: the host caps the cache length
   // paged: the page numbers of the rows this block streams, staged in LDS once (table entries
   // outside the pool are clamped into it, so a bad table cannot send a transfer out of bounds)
   int* page_s = (int*)(smem + SM::total(RB));
-  const long long page_mask = PAGED ? (1ll << p.page_shift) - 1 : 0;
-  const int slot_lo = PAGED ? (int)(((long long)t_lo * TT) >> p.page_shift) : 0;
+  const int page_mask = PAGED ? (1 << p.page_shift) - 1 : 0;
+  const int slot_lo = PAGED ? (t_lo * TT) >> p.page_shift : 0;
   if (PAGED) {
-    const int n_slots = n_blk > 0 ? (int)(row_cap >> p.page_shift) - slot_lo + 1 : 0;
+    const int n_slots = n_blk > 0 ? (row_cap >> p.page_shift) - slot_lo + 1 : 0;
     for (int i = tid; i < n_slots && i < kMaxSlicePages; i += RB * TG * 64) {
       int pg = p.block_table[(long long)b * p.max_pages + slot_lo + i];
       pg = pg < 0 ? 0 : (pg >= p.n_pool_pages ? p.n_pool_pages - 1 : pg);
@@ -381,12 +389,11 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       const int x = wave * PER + u;
       const int tt = x / (2 * NLD), which = (x / NLD) & 1, n = x % NLD;
       const int r = n * RPI + ld_row;
-      long long row = (long long)(tile0 + tt) * TT + r;
-      row = row < row_cap ? row : row_cap;
-      const char* src = (which ? vbase : kbase) + row * row_bytes;
+      const int row = min((tile0 + tt) * TT + r, row_cap);
+      const char* src = (which ? vbase : kbase) + (unsigned long long)(unsigned)row * row_bytes;   // one 32 x 32 -> 64 multiply-add
       if (PAGED)
-        src = (which ? vbase : kbase) + ((long long)page_s[(int)(row >> p.page_shift) - slot_lo] * p.page_stride +
-                                         (row & page_mask) * p.sn) * 2;
+        src = (which ? vbase : kbase) + ((long long)page_s[(row >> p.page_shift) - slot_lo] * p.page_stride +
+                                         (long long)(row & page_mask) * p.sn) * 2;
       if (APPEND && row >= p.ctx_len)                      // a row that has not reached the cache yet
         src = (const char*)(which ? p.v_new : p.k_new) +
               ((((long long)b * p.q_len + (row - p.ctx_len)) * p.Hkv + hk) * D) * 2;
@@ -405,7 +412,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       const int rr = n * QRPI + lane / QCPR;
       int r = r0 + rr;
       r = r < p.R ? r : p.R - 1;                          // padding rows repeat the last real row
-      const int i = r / p.G, gq = r % p.G;
+      const int i = row_div_group(r, inv_g), gq = r - i * p.G;
       const char* src = (const char*)p.q + ((((long long)b * p.q_len + i) * p.H + hk * p.G + gq) * D) * 2 +
                         (((lane % QCPR) ^ tile_swizzle<D, false>(rr)) * 16);
       dma16(src, q_addr + n * 1024);
@@ -415,7 +422,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
     for (int si = 1; si < issued; ++si) issue_super(si);
 
   const int row = r0 + rb * 16 + j;                       // this lane's query row
-  const int lim = (row < p.R) ? p.ctx_len + row / p.G : 0x7fffffff;
+  const int lim = (row < p.R) ? p.ctx_len + row_div_group(row, inv_g) : 0x7fffffff;
   float m_run = -INFINITY, l_run = 0.f;
   f32x4 acc[DB];
 #pragma unroll
@@ -625,7 +632,7 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
       p.part_l[slot * p.R + row] = ll;
     }
   };
-  static_assert(TG == 2 || TG == 4, "token groups");
+  static_assert(TG == 1 || TG == 2 || TG == 4, "token groups");
   if (tg == 0) finish(std::integral_constant<int, 0>());
   else if (tg == 1) finish(std::integral_constant<int, 1>());
   else if (tg == 2) finish(std::integral_constant<int, 2 % TG>());
@@ -755,7 +762,11 @@ static hipError_t launch_grid_mode(const AttnParams& p, hipStream_t st) {
     attr_set.fetch_or(bit, std::memory_order_release);
   }
   dim3 grid(p.S, p.Hkv, p.B * p.n_chunks);
-  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8, NT, ROT>), grid, dim3(RB * TG * 64), smem, st, p);
+  AttnParams q = p;                               // the slices' tile counts for this kernel's tile size
+  const int n_tiles = (p.n_total + TT - 1) / TT;
+  q.tiles_q = n_tiles / p.S;
+  q.tiles_r = n_tiles % p.S;
+  hipLaunchKernelGGL((attn_partial_grid<D, RB, TG, TT, NST, MODE, KV8, NT, ROT>), grid, dim3(RB * TG * 64), smem, st, q);
   return hipGetLastError();
 }
 

@@ -166,6 +166,7 @@ struct AttnParams {
   int S;                  // number of KV splits
   int row_chunk;          // query rows handled by one block
   int n_chunks;           // ceil(R / row_chunk)
+  int tiles_q, tiles_r;   // MFMA partial kernel: n_tiles / S and n_tiles % S (set by its launcher)
   float phase_per_head;   // 1 / (B * Hkv): (batch element, KV head) number i starts its slices i * this of the
                           // way in and wraps around; 0 = every slice is walked from its first tile
   int wave_prio;          // 1: the partial kernel's waves raise their issue priority (verification is
