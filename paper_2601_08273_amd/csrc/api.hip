@@ -84,7 +84,8 @@ int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, in
   if (S > 1024) S = 1024;
   pl->S = S;
   const size_t slots = (size_t)kv->batch * kv->n_kv_heads * S;
-  const size_t o_bytes = align_up(slots * pl->R * kv->head_dim * sizeof(float), 256);
+  // the MFMA kernel hands its slices' outputs to the merge as bf16, the vector-ALU kernel as fp32
+  const size_t o_bytes = align_up(slots * pl->R * kv->head_dim * (pl->mfma ? 2 : sizeof(float)), 256);
   const size_t ml_bytes = align_up(slots * pl->R * sizeof(float), 256);
   pl->off_m = o_bytes;
   pl->off_l = o_bytes + ml_bytes;
@@ -140,7 +141,7 @@ int attention_entry(int call, const void* q, int32_t q_len, const void* k_cache,
 
   AttnParams p;
   p.q = q; p.k = k_cache; p.v = v_cache; p.out = out; p.lse = lse_out;
-  p.part_o = reinterpret_cast<float*>(workspace);
+  p.part_o = workspace;
   p.part_m = reinterpret_cast<float*>(static_cast<char*>(workspace) + pl.off_m);
   p.part_l = reinterpret_cast<float*>(static_cast<char*>(workspace) + pl.off_l);
   p.B = kv->batch; p.q_len = q_len; p.H = kv->n_q_heads; p.Hkv = kv->n_kv_heads;

@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
 #pragma unroll
   for (int x = 0; x < RPT; ++x) {
     const int r = r0 + grp + NG * x;
-    if (r < p.R) p.part_o[(slot * p.R + r) * D + c_pv] = acc[x];
+    if (r < p.R) ((float*)p.part_o)[(slot * p.R + r) * D + c_pv] = acc[x];
   }
   if (tok == 0) {
 #pragma unroll
@@ -625,7 +625,16 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
         if (w == TGC) o += acc[TGC + TG * dd] * f[w];
         else o += other[w][dd] * f[w];
       }
-      if (row < p.R) *(f32x4*)(p.part_o + (slot * p.R + row) * D + db * 16 + 4 * g) = o;
+      // the slice's output leaves as bf16 (the merge weighs and sums it in fp32): half the bytes to write
+      // here and to fetch in the merge, and the rounding is one more of the size the output's own has
+      if (row < p.R) {
+        typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+        const f32x2_t lo = {o[0], o[1]}, hi = {o[2], o[3]};
+        uint2 w;
+        w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2_t));
+        w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2_t));
+        *(uint2*)((uint16_t*)p.part_o + (slot * p.R + row) * D + db * 16 + 4 * g) = w;
+      }
     }
     if (TGC == 0 && g == 0 && row < p.R) {
       p.part_m[slot * p.R + row] = mm;
@@ -642,13 +651,34 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
 
 // =================================================================================================
 // Merge of the KV slices: out = sum_s 2^(m_s - m*) o_s / sum_s 2^(m_s - m*) l_s
+// The slices' outputs o_s are fp32 (PO16 = false: the vector-ALU kernel's) or bf16 (the MFMA kernel's).
 // One block per (query row, KV head, batch element).  The slices are spread over the threads: first
 // the S weights (one slice per thread, block-wide max and sum), then thread (sg, vec) accumulates
 // 16-byte vector `vec` of the row over slices sg, sg + NSG, ... and the NSG groups meet in LDS.
 // =================================================================================================
 constexpr int kMaxSplits = 1024;
 
-template <typename T, int D>
+// four consecutive elements of a slice's output; for bf16 the raw bits travel in the first two components
+// until the weights are known (the loads must all be in flight before anything waits for one of them)
+template <bool PO16>
+__device__ __forceinline__ f32x4 part_o_load4(const void* base, long long elem) {
+  if constexpr (!PO16) return *(const f32x4*)((const float*)base + elem);
+  else {
+    const uint2 w = *(const uint2*)((const uint16_t*)base + elem);
+    return (f32x4){__uint_as_float(w.x), __uint_as_float(w.y), 0.f, 0.f};
+  }
+}
+template <bool PO16>
+__device__ __forceinline__ f32x4 part_o_widen(f32x4 raw) {
+  if constexpr (!PO16) return raw;
+  else {
+    const unsigned x = __float_as_uint(raw[0]), y = __float_as_uint(raw[1]);
+    return (f32x4){__uint_as_float(x << 16), __uint_as_float(x & 0xffff0000u), __uint_as_float(y << 16),
+                   __uint_as_float(y & 0xffff0000u)};
+  }
+}
+
+template <typename T, int D, bool PO16>
 __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
   constexpr int VPR = D / 4;           // float4 vectors per row
   constexpr int NSG = 256 / VPR;       // slice groups
@@ -666,9 +696,8 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
   f32x4 pre[PF];
 #pragma unroll
   for (int u = 0; u < PF; ++u) {
-    const int s = sg + u * NSG;
-    pre[u] = (s < p.S) ? *(const f32x4*)(p.part_o + ((slot0 + s) * p.R + r) * D + vec * 4)
-                       : (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int s = min(sg + u * NSG, p.S - 1);             // past the last slice: a harmless repeat, not used
+    pre[u] = part_o_load4<PO16>(p.part_o, ((slot0 + s) * p.R + r) * D + vec * 4);
   }
 
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -687,7 +716,7 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
     for (int u = 0; u < PF; ++u) {
       const int sl = sg + u * NSG;                        // < 64 whenever it is < S
       const float ws = __shfl(w, sl & 63, 64);
-      if (sl < p.S) acc += pre[u] * ws;
+      if (sl < p.S) acc += part_o_widen<PO16>(pre[u]) * ws;
     }
   } else {
     // this thread's first slice statistics ride in the same trip
@@ -718,11 +747,11 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
       const int sl = sg + u * NSG;
-      if (sl < p.S) acc += pre[u] * w_s[sl];
+      if (sl < p.S) acc += part_o_widen<PO16>(pre[u]) * w_s[sl];
     }
 #pragma unroll 4
     for (int sl = sg + PF * NSG; sl < p.S; sl += NSG) {
-      const f32x4 o = *(const f32x4*)(p.part_o + ((slot0 + sl) * p.R + r) * D + vec * 4);
+      const f32x4 o = part_o_widen<PO16>(part_o_load4<PO16>(p.part_o, ((slot0 + sl) * p.R + r) * D + vec * 4));
       acc += o * w_s[sl];
     }
   }
@@ -843,9 +872,9 @@ static hipError_t launch_valu(const AttnParams& p, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <typename T, int D>
+template <typename T, int D, bool PO16>
 static hipError_t launch_combine(const AttnParams& p, hipStream_t st) {
-  hipLaunchKernelGGL((attn_combine<T, D>), dim3(p.R, p.Hkv, p.B), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((attn_combine<T, D, PO16>), dim3(p.R, p.Hkv, p.B), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 
@@ -854,13 +883,13 @@ hipError_t launch_attention(const AttnParams& p, int dtype, int head_dim, bool u
   if (dtype == HIPPO_DTYPE_BF16) {
     if (p.k_scale != nullptr) e = (head_dim == 128) ? launch_kv8_d<128>(p, st) : launch_kv8_d<64>(p, st);
     else if (use_mfma) e = (head_dim == 128) ? launch_mfma_d<128>(p, st) : launch_mfma_d<64>(p, st);
-    else e = (head_dim == 128) ? launch_valu<uint16_t, 128>(p, st) : launch_valu<uint16_t, 64>(p, st);
+    else return hipErrorInvalidValue;       // 16- and 8-bit caches have no vector-ALU path
     if (e != hipSuccess) return e;
-    return (head_dim == 128) ? launch_combine<uint16_t, 128>(p, st) : launch_combine<uint16_t, 64>(p, st);
+    return (head_dim == 128) ? launch_combine<uint16_t, 128, true>(p, st) : launch_combine<uint16_t, 64, true>(p, st);
   }
   e = (head_dim == 128) ? launch_valu<float, 128>(p, st) : launch_valu<float, 64>(p, st);
   if (e != hipSuccess) return e;
-  return (head_dim == 128) ? launch_combine<float, 128>(p, st) : launch_combine<float, 64>(p, st);
+  return (head_dim == 128) ? launch_combine<float, 128, false>(p, st) : launch_combine<float, 64, false>(p, st);
 }
 
 }  // namespace hippo

@@ -156,7 +156,7 @@ struct AttnParams {
   const void* v;
   void* out;
   float* lse;       // may be null
-  float* part_o;    // [B, Hkv, S, R, D] unnormalised partial outputs
+  void* part_o;     // [B, Hkv, S, R, D] unnormalised partial outputs: bf16 from the MFMA kernel, fp32 from the vector-ALU kernel
   float* part_m;    // [B, Hkv, S, R] running maxima (log2 domain)
   float* part_l;    // [B, Hkv, S, R] partial denominators
   int B, q_len, H, Hkv, G, R;
