@@ -143,15 +143,11 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
       float sv = (n <= lim[x]) ? s[x] * p.scale_log2 : -INFINITY;
-      float mx = sv;
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) mx = max_nan(mx, __shfl_xor(mx, o, 64));
+      const float mx = half32_max(sv);
       const float m_new = max_nan(m_run[x], mx);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
       const float pv = fast_exp2(sv - m_safe);
-      float ps = pv;
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
+      const float ps = half32_sum(pv);
       const float a = fast_exp2(m_run[x] - m_safe);
       l_run[x] = l_run[x] * a + ps;
       m_run[x] = m_new;
@@ -700,6 +696,13 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
     pre[u] = part_o_load4<PO16>(p.part_o, ((slot0 + s) * p.R + r) * D + vec * 4);
   }
 
+  // where the row's output goes: worked out while the loads are in flight (the division would otherwise
+  // stand between the last barrier and the store)
+  const int i_row = r / p.G, h_row = hk * p.G + (r - i_row * p.G);
+  long long out_at = (((long long)b * p.q_len + i_row) * p.H + h_row) * D + (tid % VPR) * 4;
+  long long lse_at = ((long long)b * p.H + h_row) * p.q_len + i_row;
+  asm volatile("" : "+v"(out_at), "+v"(lse_at));
+
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   float mstar, den;
   if (p.S <= 64) {
@@ -762,12 +765,19 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
 #pragma unroll
     for (int g2 = 1; g2 < NSG; ++g2) t += acc_s[g2][tid];
     const float inv = 1.f / den;
-    const int i = r / p.G, gq = r % p.G, h = hk * p.G + gq;
-    T* o = (T*)p.out + (((long long)b * p.q_len + i) * p.H + h) * D + tid * 4;
+    T* o = (T*)p.out + out_at;
+    if constexpr (sizeof(T) == 2) {                        // four bf16 values: one 8-byte store
+      typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+      const f32x2_t lo = {t[0] * inv, t[1] * inv}, hi = {t[2] * inv, t[3] * inv};
+      uint2 w;
+      w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2_t));
+      w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2_t));
+      *(uint2*)o = w;
+    } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) Elem<T>::store(o + e, t[e] * inv);
-    if (p.lse != nullptr && tid == 0)
-      p.lse[((long long)b * p.H + h) * p.q_len + i] = (mstar + __log2f(den)) * kLn2;
+      for (int e = 0; e < 4; ++e) Elem<T>::store(o + e, t[e] * inv);
+    }
+    if (p.lse != nullptr && tid == 0) p.lse[lse_at] = (mstar + __log2f(den)) * kLn2;
   }
 }
 

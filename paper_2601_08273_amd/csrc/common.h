@@ -64,14 +64,48 @@ __device__ __forceinline__ float max_nan_of(const float (&v)[N]) {
 }
 
 // ---- wavefront reductions (results valid in every lane) --------------------------------------
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = max_nan(v, __shfl_xor(v, o, 64));
+// ---- cross-lane steps inside the vector ALU (data-parallel primitives, DPP) ------------------------
+// A DPP operand reads another lane of the same 16-lane row (or, for the two row broadcasts, the last
+// lane of the previous row / of the lower half) at no more than a few cycles; the generic shuffles
+// go through the LDS crossbar (ds_bpermute), a round trip of ~100 cycles per step, which is what a
+// lone wave's reduction or scan then consists of.  Lanes without a source lane, and rows outside
+// ROW_MASK, read 0.
+constexpr int kDppQuadXor1 = 0xB1;        // quad_perm [1,0,3,2]: lane ^ 1
+constexpr int kDppQuadXor2 = 0x4E;        // quad_perm [2,3,0,1]: lane ^ 2
+constexpr int kDppRowHalfMirror = 0x141;  // lane i of every 8 reads lane 7 - i
+constexpr int kDppRowMirror = 0x140;      // lane i of every 16 reads lane 15 - i
+constexpr int kDppRowShr = 0x110;         // + n: lane i reads lane i - n of its row
+constexpr int kDppRowBcast15 = 0x142;     // lane 15 of a row to every lane of the next row
+constexpr int kDppRowBcast31 = 0x143;     // lane 31 to every lane of the upper half
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ unsigned dpp_u32(unsigned v) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) { return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(v))); }
+
+// Reduction over each 16-lane row, result in all its lanes.  After lane ^ 1 and lane ^ 2 a quad is
+// uniform, so mirroring 8 lanes swaps its quads (= lane ^ 4) and mirroring the row swaps its halves.
+template <typename Op>
+__device__ __forceinline__ float row16_reduce(float v, Op op) {
+  v = op(v, dpp_f32<kDppQuadXor1>(v));
+  v = op(v, dpp_f32<kDppQuadXor2>(v));
+  v = op(v, dpp_f32<kDppRowHalfMirror>(v));
+  v = op(v, dpp_f32<kDppRowMirror>(v));
   return v;
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+__device__ __forceinline__ float row16_max(float v) { return row16_reduce(v, [](float a, float b) { return max_nan(a, b); }); }
+__device__ __forceinline__ float row16_sum(float v) { return row16_reduce(v, [](float a, float b) { return a + b; }); }
+
+// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside the rows (row_shr 1, 2, 4, 8), then
+// row 0's total into row 1 and row 2's into row 3, then the lower half's total into the upper half.
+__device__ __forceinline__ unsigned wave_scan_incl(unsigned v) {
+  v += dpp_u32<kDppRowShr + 1>(v);
+  v += dpp_u32<kDppRowShr + 2>(v);
+  v += dpp_u32<kDppRowShr + 4>(v);
+  v += dpp_u32<kDppRowShr + 8>(v);
+  v += dpp_u32<kDppRowBcast15, 0xa>(v);
+  v += dpp_u32<kDppRowBcast31, 0xc>(v);
   return v;
 }
 
@@ -92,6 +126,21 @@ __device__ __forceinline__ float rows4_sum(float v) {
   auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
+
+// over each half of the wavefront (lanes 0-31, lanes 32-63), result in all its lanes
+__device__ __forceinline__ float half32_max(float v) {
+  v = row16_max(v);
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return max_nan(__uint_as_float(a[0]), __uint_as_float(a[1]));
+}
+__device__ __forceinline__ float half32_sum(float v) {
+  v = row16_sum(v);
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(a[0]) + __uint_as_float(a[1]);
+}
+// over all 64 lanes, result in every lane
+__device__ __forceinline__ float wave_max(float v) { return rows4_max(row16_max(v)); }
+__device__ __forceinline__ float wave_sum(float v) { return rows4_sum(row16_sum(v)); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

@@ -90,12 +90,8 @@ __global__ __launch_bounds__(256) void sattn_valu(ScoreParams p) {
       const int r = r0 + rg + 8 * x;
       const float sv = tok_ok ? s[x] * scale_log2 : -INFINITY;
       if (PASS == 1) {
-        float mx = sv;
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = max_nan(mx, __shfl_xor(mx, o, 64));
-        float ps = fast_exp2(sv - mx);      // the tile always holds at least one valid token
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
+        const float mx = half32_max(sv);
+        const float ps = half32_sum(fast_exp2(sv - mx));      // the tile always holds at least one valid token
         if (tok == 0 && r < Rs) {
           const long long at = sattn_part_at(p, tile, bz, hk, r);
           p.row_m[at] = mx;
@@ -313,9 +309,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
     for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float v = col[tb][e];
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        const float v = row16_sum(col[tb][e]);
         if (j == 0 && tok_ok[tb][e])
           p.col_part[((long long)bz * p.Hkv * p.n_rsplit + vhk) * p.Nv + n0 + tb * 16 + 4 * g + e] = v;
       }

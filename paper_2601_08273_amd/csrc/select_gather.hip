@@ -42,12 +42,7 @@ __device__ __forceinline__ void walk_histogram(const unsigned* h, int nb, int la
 #pragma unroll
     for (int q = 0; q < BATCH; ++q) hsum += v[q];
   }
-  unsigned incl = hsum;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned n = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += n;
-  }
+  const unsigned incl = wave_scan_incl(hsum);
   unsigned above = incl - hsum;                 // keys in bins above this lane's
   if (above < need && incl >= need) {           // exactly one lane
     int d = top;
@@ -149,12 +144,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
       unsigned hv[BPT], hsum = 0;
 #pragma unroll
       for (int q = 0; q < BPT; ++q) { hv[q] = h[hist_slot(top - q)]; hsum += hv[q]; }
-      unsigned incl = hsum;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const unsigned n = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += n;
-      }
+      unsigned incl = wave_scan_incl(hsum);
       if (lane == 63) wave_tot[pass][wave] = incl;
       __syncthreads();
       unsigned tot[kSelWaves];
@@ -206,12 +196,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
       ce += (ok && keys[c] == thr) ? 1u : 0u;
     }
     const unsigned mine = (cg << 16) | ce;
-    unsigned incl = mine;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const unsigned n = __shfl_up(incl, o, 64);
-      if (lane >= o) incl += n;
-    }
+    const unsigned incl = wave_scan_incl(mine);
     if (lane == 63) wave_tot[0][wave] = incl;
     __syncthreads();
     unsigned tot[kSelWaves];

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from parity_util import assert_close, assert_indices_consistent, dev, host, prep
+from parity_util import assert_close, assert_fused_close, assert_indices_consistent, dev, host, prep
 
 pytestmark = pytest.mark.gpu
 
@@ -77,8 +77,8 @@ def test_scoring_and_gather_on_strided_caches(hippo, dtype):
     idx, kp, vp = hippo.hippo_select_gather_kv(scores, kk, kd, vd, vid, H, k_dst=dst[:, :, :n - nv + kk, 0],
                                                v_dst=dst[:, :, :n - nv + kk, 1])
     torch.cuda.synchronize()
-    rs, _ = oracle.score_tokens(q, k, off, F, gh, gw)
-    assert_close(host(scores), rs, dtype, "strided scores")
+    rs, rc = oracle.score_tokens(q, k, off, F, gh, gw)
+    assert_fused_close(host(scores), rs, rc, F, dtype, "strided scores")
     ridx = oracle.topk(host(scores), kk)
     np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
     np.testing.assert_array_equal(host(kp), oracle.gather(k, off, nv, ridx))

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import synth_inputs as si
-from parity_util import assert_close, dev, host
+from parity_util import assert_close, assert_fused_close, dev, host
 
 pytestmark = pytest.mark.gpu
 
@@ -40,7 +40,7 @@ def test_ablation_modes_and_border_share(hippo, name):
         idx, kp, _ = hippo.hippo_select_gather_kv(scores, cfg.k_keep, kd, vd, vid, cfg.n_q_heads)
         torch.cuda.synchronize()
         ref = oracle.fuse(sa, st, ss, cfg.n_frames, flags)
-        assert_close(host(scores), ref, dt, "%s %s" % (name, label))
+        assert_fused_close(host(scores), ref, (sa, st, ss), cfg.n_frames, dt, "%s %s" % (name, label), flags)
         np.testing.assert_array_equal(idx.cpu().numpy(), oracle.topk(host(scores), cfg.k_keep))
         assert kp.shape[2] == n - cfg.n_visual + cfg.k_keep
         share[label] = ring_share(idx.cpu().numpy(), cfg)
