@@ -243,28 +243,23 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
 }
 
 // dst row n of (b, hk): n < vis_off -> src n ; n < vis_off + k -> src vis_off + idx[n - vis_off] ;
-// else src n - k + Nv.  One thread moves 16 bytes of K and of V.
-__global__ __launch_bounds__(256) void gather_kv(SelectParams p) {
-  const int vpr = p.D * p.elem_bytes / 16;                 // 16-byte vectors per row
-  const long long total = (long long)p.B * p.Hkv * p.dst_len * vpr;
-  for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total;
-       e += (long long)gridDim.x * 256) {
-    const int vec = (int)(e % vpr);
-    long long r = e / vpr;
-    const int n = (int)(r % p.dst_len);
-    r /= p.dst_len;
-    const int hk = (int)(r % p.Hkv), b = (int)(r / p.Hkv);
-    int from;
-    if (n < p.vis_off) from = n;
-    else if (n < p.vis_off + p.k) from = p.vis_off + p.idx_out[(long long)b * p.k + (n - p.vis_off)];
-    else from = n - p.k + p.Nv;
-    const long long so = ((long long)b * p.ssb + (long long)hk * p.ssh + (long long)from * p.ssn) * p.elem_bytes;
-    const long long dof = ((long long)b * p.dsb + (long long)hk * p.dsh + (long long)n * p.dsn) * p.elem_bytes;
-    const u32x4 kv = *(const u32x4*)((const char*)p.k_src + so + vec * 16);
-    const u32x4 vv = *(const u32x4*)((const char*)p.v_src + so + vec * 16);
-    *(u32x4*)((char*)p.k_dst + dof + vec * 16) = kv;
-    *(u32x4*)((char*)p.v_dst + dof + vec * 16) = vv;
-  }
+// else src n - k + Nv.  One thread moves 16 bytes of K and of V.  Grid (rows x vectors, KV head, sequence):
+// a row holds 2^vpr_shift 16-byte vectors (head dims 64 and 128 in 1, 2 or 4 bytes), so no thread divides.
+__global__ __launch_bounds__(256) void gather_kv(SelectParams p, int vpr_shift) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  const int n = e >> vpr_shift, vec = e & ((1 << vpr_shift) - 1);
+  if (n >= p.dst_len) return;
+  const int hk = blockIdx.y, b = blockIdx.z;
+  int from;
+  if (n < p.vis_off) from = n;
+  else if (n < p.vis_off + p.k) from = p.vis_off + p.idx_out[(long long)b * p.k + (n - p.vis_off)];
+  else from = n - p.k + p.Nv;
+  const long long so = ((long long)b * p.ssb + (long long)hk * p.ssh + (long long)from * p.ssn) * p.elem_bytes;
+  const long long dof = ((long long)b * p.dsb + (long long)hk * p.dsh + (long long)n * p.dsn) * p.elem_bytes;
+  const u32x4 kv = *(const u32x4*)((const char*)p.k_src + so + vec * 16);
+  const u32x4 vv = *(const u32x4*)((const char*)p.v_src + so + vec * 16);
+  *(u32x4*)((char*)p.k_dst + dof + vec * 16) = kv;
+  *(u32x4*)((char*)p.v_dst + dof + vec * 16) = vv;
 }
 
 hipError_t launch_select_gather(const SelectParams& p, hipStream_t st) {
@@ -281,10 +276,14 @@ hipError_t launch_select_gather(const SelectParams& p, hipStream_t st) {
 #undef HIPPO_TOPK
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.k_dst == nullptr) return e;
-  const long long total = (long long)p.B * p.Hkv * p.dst_len * (p.D * p.elem_bytes / 16);
-  long long blocks = (total + 255) / 256;
-  if (blocks > 8 * 256 * 8) blocks = 8 * 256 * 8;
-  hipLaunchKernelGGL(gather_kv, dim3((unsigned)blocks), dim3(256), 0, st, p);
+  const int vpr = p.D * p.elem_bytes / 16;                 // 16-byte vectors per row: 4, 8, 16 or 32
+  int vpr_shift = 0;
+  while ((1 << vpr_shift) < vpr) ++vpr_shift;
+  if ((1 << vpr_shift) != vpr || p.Hkv > 65535 || p.B > 65535) return hipErrorInvalidValue;
+  const long long per_head = (long long)p.dst_len * vpr;
+  if (per_head == 0) return hipSuccess;
+  if ((per_head + 255) / 256 > 0x7fffffffll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gather_kv, dim3((unsigned)((per_head + 255) / 256), p.Hkv, p.B), dim3(256), 0, st, p, vpr_shift);
   return hipGetLastError();
 }
 
