@@ -17,12 +17,15 @@ constexpr int kBins = 4096;              // 12-bit digits (the last pass uses 25
 constexpr int kHistStride = kBins + kBins / 64;   // padded histogram
 __device__ __forceinline__ int hist_slot(int bin) { return bin + (bin >> 6); }
 
-// larger score -> larger key; -0 == +0; NaN -> 0, below every number (-inf maps to 0x007fffff)
+// larger score -> larger key; -0 == +0; NaN -> 1, below every number (-inf maps to 0x00800000).
+// No score maps to key 0: a thread's slots past the end of the sequence hold 0, which lies below
+// every real key, so with k <= N_v such a slot is never above or equal to the k-th largest key and
+// no sweep over the cached keys has to ask whether a slot is real.
 __device__ __forceinline__ uint32_t score_key(float x) {
-  if (x != x) return 0u;
+  if (x != x) return 1u;
   uint32_t u = __float_as_uint(x);
   if ((u << 1) == 0u) u = 0u;
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((u & 0x80000000u) ? ~u : (u | 0x80000000u)) + 1u;      // at most 0xff800001 (+inf)
 }
 
 // One wave walks a histogram from the top bin down (no barriers inside): lane l owns the BPL bins
@@ -65,46 +68,82 @@ __device__ __forceinline__ void walk_histogram(const unsigned* h, int nb, int la
   }
 }
 
-// One block per sequence.  NC > 0: every thread keeps NC consecutive keys (indices tid*NC ..) in
-// registers, so the scores are read from memory once and every loop over them is unrolled to the
-// sequence's size class; NC = 0: any length, keys strided over the threads, each pass re-reads them.
+// Exclusive prefix of `mine` over the block's threads in thread order: a wave scan, the wave totals
+// through LDS (one barrier), and the totals of the waves in front by a 16-lane row scan of the totals
+// and one lane read.  tot = 16 words nobody else touches until the next barrier.
+// sum of the totals of the waves in front of this one (wave_total is wave-uniform)
+__device__ __forceinline__ unsigned waves_in_front(unsigned wave_total, unsigned* tot, int lane, int wave) {
+  if (lane == 63) tot[wave] = wave_total;
+  __syncthreads();
+  unsigned t = tot[lane & (kSelWaves - 1)];
+  t += dpp_u32<kDppRowShr + 1>(t);
+  t += dpp_u32<kDppRowShr + 2>(t);
+  t += dpp_u32<kDppRowShr + 4>(t);
+  t += dpp_u32<kDppRowShr + 8>(t);
+  static_assert(kSelWaves == 16, "the wave totals fill one 16-lane row");
+  const int w = __builtin_amdgcn_readfirstlane(wave);
+  return w > 0 ? (unsigned)__builtin_amdgcn_readlane((int)t, w - 1) : 0u;
+}
+__device__ __forceinline__ unsigned block_scan_excl(unsigned mine, unsigned* tot, int lane, int wave) {
+  const unsigned incl = wave_scan_incl(mine);
+  return incl - mine + waves_in_front((unsigned)__builtin_amdgcn_readlane((int)incl, 63), tot, lane, wave);
+}
+
+// One block per sequence.  NC > 0: every thread keeps NC keys in registers, so the scores are read
+// from memory once and every loop over them is unrolled to the sequence's size class.  A wave owns
+// 64 NC consecutive scores, dealt to its lanes VW at a time (slot c of lane l is score
+// wave*64*NC + ((c / VW)*64 + l)*VW + c % VW), so that each load instruction of a wave reads one
+// contiguous kilobyte; NC = 0: any length, keys strided over the threads, each pass re-reads them.
 // Radix select with digits of 12, 12 and 8 bits: the wide first digit (sign, exponent, 3 mantissa
 // bits) spreads scores of similar magnitude over many LDS bins, which keeps same-address atomic
-// traffic low.  The compaction is index-ordered: per-thread counts and one scan when the keys are
-// cached, per-(chunk, wave) ballots with running totals otherwise.
+// traffic low.  With cached keys, the keys that share the first digit with the k-th largest (a few
+// hundred of 16K on scores of unit scale) are copied to an LDS list when they fit, and the second and
+// third histogram are built from that list instead of from another sweep over every thread's keys.
+// The compaction is index-ordered: when the keys are cached, one wave scan per group of VW slots plus
+// one scan of the wave totals, per-(chunk, wave) ballots with running totals otherwise.
 template <int NC>
 __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   constexpr bool CACHED = NC > 0;
   // one histogram per radix pass (12, 12, 8 bits); bin i lives at i + i/64, so that the 64 lanes of
   // the scanning wave, which own runs of 64 consecutive bins, hit different LDS banks
-  __shared__ unsigned hist[2 * kHistStride + 256 + 4];
+  constexpr int kHistWords = 2 * kHistStride + 256 + 4;
+  constexpr int kListCap = kBins;            // candidate list: the first histogram's memory, once its digit is known
+  __shared__ unsigned hist[kHistWords];
   __shared__ unsigned wave_tot[2][kSelWaves];
-  __shared__ unsigned sh_prefix, sh_need;
+  __shared__ unsigned sh_prefix, sh_need, sh_bin_count, sh_list_n;
 
   const int b = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const float* sc = p.scores + (long long)b * p.Nv;
   int32_t* out = p.idx_out + (long long)b * p.k;
   const int n_chunks = (p.Nv + kSelThreads - 1) / kSelThreads;
-  // CACHED: thread t owns the NC consecutive scores t*NC .. t*NC+NC-1 (index order = thread order,
-  // which makes the compaction a per-thread count plus one scan); 16-byte loads where the row allows
-  unsigned keys[CACHED ? NC : 1];
-  const int first = tid * NC;                // CACHED only
+  // CACHED: every load goes out before anything waits for one: 16-byte loads where the row allows,
+  // addresses past the end pulled back inside (those slots are then set to 0), and the histograms are
+  // cleared under the loads.
+  constexpr int VW = !CACHED ? 1 : (NC % 4 == 0 ? 4 : (NC % 2 == 0 ? 2 : 1));    // slots dealt together
+  constexpr int NV = CACHED ? NC / VW : 1;
+  unsigned keys[CACHED ? NC : 1];            // first the scores' bits, then, in place, their keys
+  const int wave_first = wave * 64 * NC;     // CACHED only
+  auto slot_index = [&](int c) { return wave_first + ((c / VW) * 64 + lane) * VW + c % VW; };
   if (CACHED) {
-    const bool vec_ok = (NC % 4 == 0) && ((((long long)b * p.Nv) & 3) == 0) &&
-                        ((reinterpret_cast<uintptr_t>(p.scores) & 15u) == 0);
+    const bool vec_ok = (VW == 4) && (p.Nv % 4 == 0) && ((((long long)b * p.Nv) & 3) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(p.scores) & 15u) == 0);      // block-uniform
+    if (vec_ok) {
 #pragma unroll
-    for (int c0 = 0; c0 < NC; c0 += 4) {
-      if (NC % 4 == 0 && vec_ok && first + c0 + 3 < p.Nv) {
-        const f32x4 v = *(const f32x4*)(sc + first + c0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) keys[c0 + e] = score_key(v[e]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (c0 + e < NC) keys[c0 + e] = (first + c0 + e < p.Nv) ? score_key(sc[first + c0 + e]) : 0u;
+      for (int v = 0; v < NV; ++v) {
+        const u32x4 x = *(const u32x4*)(sc + min(slot_index(v * VW), p.Nv - 4));
+        keys[v * VW] = x.x; keys[v * VW + 1 % VW] = x.y; keys[v * VW + 2 % VW] = x.z; keys[v * VW + 3 % VW] = x.w;
       }
+    } else {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) keys[c] = __float_as_uint(sc[min(slot_index(c), p.Nv - 1)]);
     }
+  }
+  for (int i = tid; i < kHistWords; i += kSelThreads) hist[i] = 0;
+  if (tid == 0) sh_list_n = 0;
+  if (CACHED) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) keys[c] = (slot_index(c) < p.Nv) ? score_key(__uint_as_float(keys[c])) : 0u;
   }
   auto key_at = [&](int c) -> unsigned {     // NC = 0: key of chunk c for this thread (index must be < Nv)
     return score_key(sc[c * kSelThreads + tid]);
@@ -114,16 +153,22 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
   const int shifts[3] = {20, 8, 0};
   const unsigned masks[3] = {0u, 0xfff00000u, 0xffffff00u};   // bits already decided
   const unsigned dmask[3] = {0xfffu, 0xfffu, 0xffu};
-  // the three histograms are cleared once, up front
-  for (int i = tid; i < 2 * kHistStride + 256 + 4; i += kSelThreads) hist[i] = 0;
+  bool listed = false;                         // block-uniform: the candidates are in the LDS list
+  unsigned list_n = 0;
+  unsigned* const list = hist;                 // the first histogram's words
   __syncthreads();
 #pragma unroll
   for (int pass = 0; pass < 3; ++pass) {
     unsigned* h = hist + (pass == 0 ? 0 : pass == 1 ? kHistStride : 2 * kHistStride);
-    if (CACHED) {
+    if (CACHED && pass > 0 && listed) {
+      for (unsigned i = tid; i < list_n; i += kSelThreads) {
+        const unsigned key = list[i];
+        if ((key & masks[pass]) == prefix) atomicAdd(&h[hist_slot((key >> shifts[pass]) & dmask[pass])], 1u);
+      }
+    } else if (CACHED) {
 #pragma unroll
-      for (int c = 0; c < NC; ++c)
-        if (first + c < p.Nv && (keys[c] & masks[pass]) == prefix)
+      for (int c = 0; c < NC; ++c)        // (slots past the end would all hit bin 0: the first pass leaves them out)
+        if ((keys[c] & masks[pass]) == prefix && (pass > 0 || keys[c] != 0u))
           atomicAdd(&h[hist_slot((keys[c] >> shifts[pass]) & dmask[pass])], 1u);
     } else {
       for (int c = 0; c < n_chunks; ++c)
@@ -144,32 +189,46 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
       unsigned hv[BPT], hsum = 0;
 #pragma unroll
       for (int q = 0; q < BPT; ++q) { hv[q] = h[hist_slot(top - q)]; hsum += hv[q]; }
-      unsigned incl = wave_scan_incl(hsum);
-      if (lane == 63) wave_tot[pass][wave] = incl;
-      __syncthreads();
-      unsigned tot[kSelWaves];
-#pragma unroll
-      for (int w = 0; w < kSelWaves; ++w) tot[w] = wave_tot[pass][w];     // independent reads, one wait
-#pragma unroll
-      for (int w = 0; w < kSelWaves; ++w) incl += (w < wave) ? tot[w] : 0u;
-      unsigned above = incl - hsum;
-      if (above < need && incl >= need) {                   // exactly one thread
+      unsigned above = block_scan_excl(hsum, wave_tot[pass], lane, wave);
+      if (above < need && above + hsum >= need) {           // exactly one thread
         int d = top;
+        unsigned in_bin = 0;
         bool found = false;
 #pragma unroll
         for (int q = 0; q < BPT; ++q) {
           if (!found) {
-            if (above + hv[q] >= need) { found = true; d = top - q; }
+            if (above + hv[q] >= need) { found = true; d = top - q; in_bin = hv[q]; }
             else above += hv[q];
           }
         }
         sh_prefix = prefix | ((unsigned)d << shifts[pass]);
         sh_need = need - above;
+        sh_bin_count = in_bin;
       }
     }
     __syncthreads();
     prefix = sh_prefix;
     need = sh_need;
+    if (CACHED && pass == 0 && sh_bin_count <= (unsigned)kListCap && prefix != 0u) {   // (digit 0 would match empty slots)
+      // the keys that share the first digit with the k-th largest move to the list (the first
+      // histogram is spent): per-thread count, wave scan, one LDS atomic per wave for its base.
+      // The order of the list does not matter: only histograms are built from it.
+      unsigned m = 0;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) m += ((keys[c] & masks[1]) == prefix) ? 1u : 0u;
+      const unsigned incl = wave_scan_incl(m);
+      unsigned base = 0;
+      if (lane == 63 && incl > 0) base = atomicAdd(&sh_list_n, incl);
+      unsigned at = (unsigned)__builtin_amdgcn_readlane((int)base, 63) + incl - m;
+      if (m > 0) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+          if ((keys[c] & masks[1]) == prefix) list[at++] = keys[c];
+      }
+      listed = true;
+      list_n = sh_bin_count;
+      __syncthreads();
+    }
   }
   const unsigned thr = prefix;      // the k-th largest key
   const unsigned need_eq = need;    // how many keys equal to it are kept (lowest indices first)
@@ -185,32 +244,31 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     }
   };
   if (CACHED) {
-    // per-thread counts of keys above / equal to the threshold, packed (both fit 16 bits: a block
-    // caches at most 40960 keys), one block-wide exclusive scan, then every thread writes its own
-    // survivors in order
-    unsigned cg = 0, ce = 0;
+    // counts of keys above / equal to the threshold, packed (both fit 16 bits: a block caches at
+    // most 40960 keys).  Index order inside a wave is (group of VW slots, lane, slot in the group):
+    // one wave scan per group, a running total over the groups, then the totals of the waves in
+    // front; every thread then writes its own survivors.
+    unsigned excl[NV], run = 0;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const bool ok = first + c < p.Nv;
-      cg += (ok && keys[c] > thr) ? 1u : 0u;
-      ce += (ok && keys[c] == thr) ? 1u : 0u;
+    for (int v = 0; v < NV; ++v) {
+      unsigned mine = 0;
+#pragma unroll
+      for (int e = 0; e < VW; ++e)
+        mine += ((keys[v * VW + e] > thr) ? 0x10000u : 0u) + ((keys[v * VW + e] == thr) ? 1u : 0u);
+      const unsigned incl = wave_scan_incl(mine);
+      excl[v] = run + incl - mine;
+      run += (unsigned)__builtin_amdgcn_readlane((int)incl, 63);
     }
-    const unsigned mine = (cg << 16) | ce;
-    const unsigned incl = wave_scan_incl(mine);
-    if (lane == 63) wave_tot[0][wave] = incl;
-    __syncthreads();
-    unsigned tot[kSelWaves];
+    const unsigned in_front = waves_in_front(run, wave_tot[0], lane, wave);
+    int32_t* const dst = out;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) tot[w] = wave_tot[0][w];
-    unsigned before = incl - mine;
+    for (int v = 0; v < NV; ++v) {
+      unsigned gt_before = (in_front + excl[v]) >> 16, eq_before = (in_front + excl[v]) & 0xffffu;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) before += (w < wave) ? tot[w] : 0u;
-    unsigned gt_before = before >> 16, eq_before = before & 0xffffu;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      if (first + c < p.Nv) {
-        const bool gt = keys[c] > thr, eq = keys[c] == thr;
-        if (gt || (eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = first + c;
+      for (int e = 0; e < VW; ++e) {
+        const unsigned key = keys[v * VW + e];
+        const bool gt = key > thr, eq = key == thr;
+        if (gt || (eq && eq_before < need_eq)) dst[gt_before + min(eq_before, need_eq)] = slot_index(v * VW + e);
         gt_before += gt ? 1u : 0u;
         eq_before += eq ? 1u : 0u;
       }
