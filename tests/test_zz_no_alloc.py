@@ -37,7 +37,7 @@ def _both(hippo, q, k, v, ctx, num_splits=0):
 
 def test_static_scratch_matches_the_workspace_call_twice_in_a_row(hippo):
     assert hippo.load().hippo_static_scratch_init() == hippo.OK
-    # first the 16K headline shape (64 slices per KV head, 5.6 MB of partials), then a much smaller one
+    # first the 16K headline shape (64 slices per KV head, 2.9 MB of partials), then a much smaller one
     # whose partials cover only the front of the array the first call filled
     big, small = si.CONFIGS["c3_16k"], si.CONFIGS["draft"]
     for cfg, splits in ((big, 0), (small, 0), (small, 5), (big, 0)):
