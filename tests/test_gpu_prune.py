@@ -148,6 +148,22 @@ def test_topk_with_many_ties(hippo, n, k, distinct):
     select_case(hippo, si.random_scores(3, n, n, n_distinct=distinct), k)
 
 
+@pytest.mark.parametrize("n,k,others", [(3000, 300, 0), (4096, 1000, 0), (4097, 1000, 0), (4200, 150, 104),
+                                        (16384, 1639, 37), (33000, 3300, 5000), (40960, 40000, 1)])
+def test_topk_scores_sharing_the_first_digit(hippo, n, k, others):
+    """Scores whose keys agree in sign, exponent and the top three mantissa bits: the radix select's first digit
+    does not separate them.  The sizes put 3000, exactly 4096, 4097 and many more keys into that one bin (the
+    boundary of the in-LDS candidate list and the register sweeps beyond it); `others` scores lie elsewhere, above
+    and below, so the wanted key is in the crowded bin for some cases and next to it for others."""
+    rng = np.random.default_rng(n + k)
+    s = (1.0 + rng.random((2, n)) * 0.0624).astype(np.float32)          # [1, 1.0625): one 12-bit digit
+    s[1] = np.round(s[1] * 64) / 64                                       # second row: a handful of distinct values
+    if others:
+        at = rng.choice(n, size=others, replace=False)
+        s[:, at] = (rng.standard_normal((2, others)) * 3).astype(np.float32)
+    select_case(hippo, s, k)
+
+
 def test_topk_special_values(hippo):
     s = si.random_scores(4, 3000, 9)
     s[0, ::5] = np.nan
