@@ -63,8 +63,8 @@ __device__ __forceinline__ float max_nan_of(const float (&v)[N]) {
   return m;
 }
 
-// ---- wavefront reductions (results valid in every lane) --------------------------------------
-// ---- cross-lane steps inside the vector ALU (data-parallel primitives, DPP) ------------------------
+// ---- wavefront reductions and scans (results valid in every lane) ----------------------------
+// Cross-lane steps inside the vector ALU (data-parallel primitives, DPP):
 // A DPP operand reads another lane of the same 16-lane row (or, for the two row broadcasts, the last
 // lane of the previous row / of the lower half) at no more than a few cycles; the generic shuffles
 // go through the LDS crossbar (ds_bpermute), a round trip of ~100 cycles per step, which is what a
@@ -137,6 +137,18 @@ __device__ __forceinline__ float half32_sum(float v) {
   v = row16_sum(v);
   auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float(a[0]) + __uint_as_float(a[1]);
+}
+// exact integer reduction (op associative and commutative: min, max, or, ...) over all 64 lanes
+template <typename Op>
+__device__ __forceinline__ int wave_reduce_i32(int v, Op op) {
+  v = op(v, (int)dpp_u32<kDppQuadXor1>((unsigned)v));
+  v = op(v, (int)dpp_u32<kDppQuadXor2>((unsigned)v));
+  v = op(v, (int)dpp_u32<kDppRowHalfMirror>((unsigned)v));
+  v = op(v, (int)dpp_u32<kDppRowMirror>((unsigned)v));
+  auto a = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+  v = op((int)a[0], (int)a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+  return op((int)b[0], (int)b[1]);
 }
 // over all 64 lanes, result in every lane
 __device__ __forceinline__ float wave_max(float v) { return rows4_max(row16_max(v)); }

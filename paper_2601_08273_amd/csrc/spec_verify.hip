@@ -23,6 +23,39 @@
 namespace hippo {
 
 namespace {
+// (largest value, lowest index among equals) of the lanes' candidates: an exact, order-independent
+// choice, so the steps can run in any order -- inside the vector ALU: four in-row steps, two row swaps
+__device__ __forceinline__ void better_of(float& m, int& arg, float om, int oa) {
+  if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
+}
+template <int CTRL>
+__device__ __forceinline__ void argmax_step(float& m, int& arg) {
+  const float om = dpp_f32<CTRL>(m);
+  const int oa = (int)dpp_u32<CTRL>((unsigned)arg);
+  better_of(m, arg, om, oa);
+}
+__device__ __forceinline__ void row16_argmax(float& m, int& arg) {
+  argmax_step<kDppQuadXor1>(m, arg);
+  argmax_step<kDppQuadXor2>(m, arg);
+  argmax_step<kDppRowHalfMirror>(m, arg);
+  argmax_step<kDppRowMirror>(m, arg);
+}
+__device__ __forceinline__ void wave_argmax(float& m, int& arg) {
+  row16_argmax(m, arg);
+  {
+    auto sm = __builtin_amdgcn_permlane16_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+    auto sa = __builtin_amdgcn_permlane16_swap((unsigned)arg, (unsigned)arg, false, false);
+    m = __uint_as_float(sm[0]); arg = (int)sa[0];
+    better_of(m, arg, __uint_as_float(sm[1]), (int)sa[1]);
+  }
+  {
+    auto sm = __builtin_amdgcn_permlane32_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+    auto sa = __builtin_amdgcn_permlane32_swap((unsigned)arg, (unsigned)arg, false, false);
+    m = __uint_as_float(sm[0]); arg = (int)sa[0];
+    better_of(m, arg, __uint_as_float(sm[1]), (int)sa[1]);
+  }
+}
+
 
 constexpr int kSdThreads = 256;
 constexpr int kSdWaves = kSdThreads / 64;
@@ -80,12 +113,7 @@ __global__ __launch_bounds__(kSdThreads) void sd_row_stats(SpecParams p) {
     const int idx = v0 + ((i / VEC) * kSdThreads + tid) * VEC + (i % VEC);
     if (x[i] > m) { m = x[i]; arg = idx; }
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float om = __shfl_xor(m, o, 64);
-    const int oa = __shfl_xor(arg, o, 64);
-    if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
-  }
+  wave_argmax(m, arg);
   if (lane == 0) { sh_m[wave] = m; sh_a[wave] = arg; }
   __syncthreads();
   m = sh_m[0]; arg = sh_a[0];
@@ -158,12 +186,7 @@ __global__ __launch_bounds__(kSdThreads) void sd_cells(SpecParams p) {
         const int sa_ = rs[i].arg;
         if (sm_ > m || (sm_ == m && sa_ < arg)) { m = sm_; arg = sa_; }
       }
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) {
-        const float om = __shfl_xor(m, o, 64);
-        const int oa = __shfl_xor(arg, o, 64);
-        if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
-      }
+      row16_argmax(m, arg);
       float z = 0.f;
       if (!greedy)
         for (int i = gl; i < p.n_seg; i += 16)
@@ -320,11 +343,8 @@ __global__ __launch_bounds__(kSdThreads) void sd_pick(SpecParams p) {
   }
   sh_before[tid] = before_first;
   int wf = first, wl = last;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    wf = min(wf, __shfl_xor(wf, o, 64));
-    wl = max(wl, __shfl_xor(wl, o, 64));
-  }
+  wf = wave_reduce_i32(wf, [](int a, int b) { return min(a, b); });
+  wl = wave_reduce_i32(wl, [](int a, int b) { return max(a, b); });
   if (lane == 0) { sh_first[wave] = wf; sh_last[wave] = wl; }
   __syncthreads();
   if (wave != 0) return;
@@ -372,11 +392,8 @@ __global__ __launch_bounds__(kSdThreads) void sd_pick(SpecParams p) {
     run_l += val[e];
     if (hit == 0x7fffffff && val[e] > 0.f && run_l > target) hit = w0 + e;
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    hit = min(hit, __shfl_xor(hit, o, 64));
-    last_w = max(last_w, __shfl_xor(last_w, o, 64));
-  }
+  hit = wave_reduce_i32(hit, [](int a, int b) { return min(a, b); });
+  last_w = wave_reduce_i32(last_w, [](int a, int b) { return max(a, b); });
   if (lane == 0) p.next_token[b] = (hit != 0x7fffffff) ? hit : (last_w >= 0 ? last_w : 0);
 }
 
