@@ -196,7 +196,9 @@ int hippo_select_gather_kv(const float* scores, int32_t k,
  * q, out [B, q_len, H, d] contiguous, dtype kv->dtype.  lse_out optional [B, H, q_len] fp32: natural
  * log of the softmax denominator (of the scaled logits).  softmax_scale <= 0 means 1/sqrt(d).
  * num_splits: how many slices the KV range is cut into (flash-decoding style), 0 = library's
- * choice; the result does not depend on it beyond fp32 rounding.  ctx_len >= 0, q_len >= 1.
+ * choice; the result does not depend on it beyond rounding (fp32 caches: fp32 throughout; 16- and 8-bit
+ * caches: each slice's output reaches the merge rounded to bf16, its statistics in fp32).
+ * ctx_len >= 0, q_len >= 1.
  * Errors: NULL_ARG, BAD_SHAPE, BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
  */
 int hippo_verify_attention(const void* q, int32_t q_len,
