@@ -125,10 +125,10 @@ constexpr int kSaWaves = 8;           // waves per block, 32 tokens each: two wa
 template <int D, int PASS>
 struct SattnSmem {
   static constexpr int RCH = 64;                 // query rows per LDS chunk
-  static constexpr int ROWB = D * 2 + 16;
+  static constexpr int ROWB = D * 2;             // unpadded rows, 16-byte pieces XOR-swizzled (lds_row_swizzle)
   static constexpr int RDEF = 256;               // pass 1 merges the waves' row statistics every RDEF rows
-  __align__(16) unsigned char Qs[RCH * ROWB];
-  float lse_s[RCH];
+  __align__(16) unsigned char Qs[2][RCH * ROWB]; // two chunks: the next one lands while this one is multiplied
+  float lse_s[2][RCH];
   float wm_s[PASS == 1 ? kSaWaves : 1][PASS == 1 ? RDEF : 1];
   float wl_s[PASS == 1 ? kSaWaves : 1][PASS == 1 ? RDEF : 1];
 };
@@ -145,8 +145,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
   constexpr int CPR = D / 8;
   constexpr int RCH = SattnSmem<D, PASS>::RCH;
   constexpr int RDEF = SattnSmem<D, PASS>::RDEF;
-  unsigned char* Qs = sm.Qs;
-  float* lse_s = sm.lse_s;
+  unsigned char* Qs = &sm.Qs[0][0];
   auto& wm_s = sm.wm_s;
   auto& wl_s = sm.wl_s;
 
@@ -187,31 +186,42 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 #pragma unroll
     for (int e = 0; e < 4; ++e) col[tb][e] = 0.f;
 
-  // query rows are staged 64 at a time; the next chunk is fetched into registers while the
-  // current one is being multiplied, so the trip to memory hides behind the MFMAs
-  constexpr int QPT = (RCH * CPR + NT - 1) / NT;   // 16-byte pieces per thread per chunk
-  u32x4 qreg[QPT];
+  // Query rows are staged 64 at a time, straight from memory into LDS (16 bytes per lane, no
+  // registers in between): a transfer fills 1 KB, i.e. 64 / CPR whole rows, and the chunk after the
+  // current one is requested as soon as every wave has left the chunk before it, so its trip to
+  // memory hides behind the MFMAs and a chunk costs one barrier.
+  constexpr int RPI = 64 / CPR;                    // rows per transfer
+  constexpr int XPW = RCH / RPI / NW;              // transfers per wave per chunk
+  static_assert(RCH % (RPI * NW) == 0, "a chunk's transfers must split over the waves");
+  constexpr int CHUNKB = RCH * ROWB;
+  const unsigned qs_addr = (unsigned)(uintptr_t)Qs;
   float lse_reg = INFINITY;
   // Row r = i*G + g of the KV head lives at ((b*L + i)*H + hk*G + g)*D.  The (i, g) of the rows this
-  // thread stages are carried from chunk to chunk (a chunk advances every row by RCH), so the
-  // division by G happens once, not per chunk.
+  // lane requests are carried from chunk to chunk (a chunk advances every row by RCH), so the
+  // division by G happens once, not per chunk.  Rows past the end re-read the last row: pass 1 does
+  // not write their statistics and pass 2 gives them an infinite normaliser.
   const uint16_t* qbase = (const uint16_t*)p.q_layers[layer] + ((long long)b * p.L * p.H + hk * p.G) * D;
-  int qi[QPT], qg[QPT];
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  int qi[XPW], qg[XPW], qr[XPW];
+  unsigned qpiece[XPW];                            // byte offset of this lane's piece inside its source row
   const int step_i = RCH / p.G, step_g = RCH % p.G;
+  const int last_i = (Rs - 1) / p.G, last_g = (Rs - 1) % p.G;
 #pragma unroll
-  for (int u = 0; u < QPT; ++u) {
-    const int r = row_begin + (tid + NT * u) / CPR;
-    qi[u] = r / p.G;
-    qg[u] = r % p.G;
+  for (int u = 0; u < XPW; ++u) {
+    const int rr = (wave_u * XPW + u) * RPI + lane / CPR;       // row inside the chunk
+    qr[u] = row_begin + rr;
+    qi[u] = qr[u] / p.G;
+    qg[u] = qr[u] % p.G;
+    qpiece[u] = (unsigned)(((lane % CPR) ^ lds_row_swizzle<D>(rr)) * 16);
   }
-  auto fetch_chunk = [&](int r0) {             // must be called with r0 = row_begin, +RCH, +2 RCH, ...
+  auto request_chunk = [&](int buf, int r0) {    // must be called with r0 = row_begin, +RCH, +2 RCH, ...
 #pragma unroll
-    for (int u = 0; u < QPT; ++u) {
-      const int e = tid + NT * u;
-      const int r = r0 + e / CPR;
-      qreg[u] = (u32x4){0u, 0u, 0u, 0u};
-      if (e < RCH * CPR && r < Rs)
-        qreg[u] = *(const u32x4*)(qbase + ((long long)qi[u] * p.H + qg[u]) * D + (e % CPR) * 8);
+    for (int u = 0; u < XPW; ++u) {
+      const bool real = qr[u] < Rs;
+      const int i = real ? qi[u] : last_i, g2 = real ? qg[u] : last_g;
+      dma16((const char*)(qbase + ((long long)i * p.H + g2) * D) + qpiece[u],
+            qs_addr + buf * CHUNKB + (wave_u * XPW + u) * 1024);
+      qr[u] += RCH;
       qg[u] += step_g;
       const int carry = qg[u] >= p.G ? 1 : 0;
       qg[u] -= carry * p.G;
@@ -223,24 +233,23 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
       if (r < Rs) lse_reg = p.row_lse[((long long)bz * p.Hkv + hk) * Rs + r];
     }
   };
-  fetch_chunk(row_begin);
-  for (int r0 = row_begin; r0 < row_end; r0 += RCH) {
-    __syncthreads();                          // everyone is done with the previous chunk
-#pragma unroll
-    for (int u = 0; u < QPT; ++u) {
-      const int e = tid + NT * u;
-      if (e < RCH * CPR) *(u32x4*)(Qs + (e / CPR) * ROWB + (e % CPR) * 16) = qreg[u];
-    }
-    if (PASS == 2 && tid < RCH) lse_s[tid] = lse_reg;
-    __syncthreads();
-    if (r0 + RCH < row_end) fetch_chunk(r0 + RCH);
+  if (row_begin < row_end) request_chunk(0, row_begin);     // (every request is waited for at the top of its chunk)
+  int buf = 0;
+  for (int r0 = row_begin; r0 < row_end; r0 += RCH, buf ^= 1) {
+    wait_vmcnt<0>();                          // this wave's share of the chunk (and its normalisers) has arrived
+    if (PASS == 2 && tid < RCH) sm.lse_s[buf][tid] = lse_reg;
+    __syncthreads();                          // ... and everyone else's; everyone is done with the chunk before
+    if (r0 + RCH < row_end) request_chunk(buf ^ 1, r0 + RCH);
+    const unsigned char* Qc = Qs + buf * CHUNKB;
+    const float* lse_c = sm.lse_s[buf];
 
     auto products = [&](int rb, f32x4 (&z)[TBW]) {
 #pragma unroll
       for (int tb = 0; tb < TBW; ++tb) z[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 qop = *(const bf16x8*)(Qs + (rb * 16 + j) * ROWB + (g * KS + ks) * 16);
+        const bf16x8 qop = *(const bf16x8*)(Qc + (rb * 16 + j) * ROWB +
+                                            (((g * KS + ks) ^ lds_row_swizzle<D>(rb * 16 + j)) * 16));
 #pragma unroll
         for (int tb = 0; tb < TBW; ++tb)
           z[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[tb][ks], qop, z[tb], 0, 0, 0);
@@ -272,7 +281,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
           wl_s[wave][((r0 - row_begin) % RDEF) + rb * 16 + j] = ps;
         }
       } else {
-        const float lse = lse_s[rb * 16 + j];
+        const float lse = lse_c[rb * 16 + j];
 #pragma unroll
         for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
