@@ -676,7 +676,7 @@ __device__ __forceinline__ f32x4 part_o_widen(f32x4 raw) {
 
 template <typename T, int D, bool PO16>
 __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
-  constexpr int VPR = D / 4;           // float4 vectors per row
+  constexpr int VPR = D / 4;           // four-element vectors per row
   constexpr int NSG = 256 / VPR;       // slice groups
   __shared__ float w_s[kMaxSplits];
   __shared__ float red[8];

@@ -37,8 +37,10 @@ __global__ __launch_bounds__(kQuantThreads) void kv_absmax(QuantParams p) {
   const int which = blockIdx.y & 1, hk = blockIdx.y >> 1, b = blockIdx.z;
   const T* src = (const T*)(which ? p.v_src : p.k_src) + (long long)b * p.ssb + (long long)hk * p.ssh;
   constexpr int PV = Elem<T>::kPerVec;
-  const int vpr = p.D / PV;
-  const long long n_vec = (long long)p.n_rows * vpr;
+  // a row holds 2^vshift 16-byte vectors (head dims 64 and 128): rows and vectors part by a shift,
+  // the slice bounds are the only division of the kernel
+  const int vshift = __builtin_ctz(p.D / PV), vmask = (1 << vshift) - 1;
+  const long long n_vec = (long long)p.n_rows << vshift;
   const long long per = (n_vec + gridDim.x - 1) / gridDim.x;
   const long long lo = (long long)blockIdx.x * per, hi = min(n_vec, lo + per);
   float m = 0.f;
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(kQuantThreads) void kv_absmax(QuantParams p) {
     for (int u = 0; u < 4; ++u) {
       const long long e = e0 + u * kQuantThreads;
       v[u] = (u32x4){0u, 0u, 0u, 0u};
-      if (e < hi) v[u] = *(const u32x4*)(src + (e / vpr) * p.ssn + (int)(e % vpr) * PV);
+      if (e < hi) v[u] = *(const u32x4*)(src + (e >> vshift) * p.ssn + ((int)e & vmask) * PV);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) m = fmaxf(m, vec_absmax<T>(v[u]));
@@ -76,24 +78,35 @@ __global__ __launch_bounds__(kQuantThreads) void kv_encode(QuantParams p) {
   unsigned char* dst = (unsigned char*)(which ? p.v_dst : p.k_dst) + (long long)b * p.dsb + (long long)hk * p.dsh;
   constexpr int PV = Elem<T>::kPerVec;
   constexpr int SV = 16 / PV;                         // source vectors per 16 codes
-  const int cpr = p.D / 16;                           // 16-byte code vectors per row
-  const long long n_vec = (long long)p.n_rows * cpr;
+  const int cshift = __builtin_ctz(p.D / 16), cmask = (1 << cshift) - 1;   // 2^cshift 16-byte code vectors per row
+  const long long n_vec = (long long)p.n_rows << cshift;
   const long long per = (n_vec + gridDim.x - 1) / gridDim.x;
   const long long lo = (long long)blockIdx.x * per, hi = min(n_vec, lo + per);
-  for (long long e = lo + threadIdx.x; e < hi; e += kQuantThreads) {
-    const long long row = e / cpr;
-    const int vec = (int)(e % cpr);
-    float x[16];
+  for (long long e0 = lo + threadIdx.x; e0 < hi; e0 += 4 * kQuantThreads) {
+    u32x4 raw[4][SV];                                      // every load of four code vectors in flight at once
 #pragma unroll
-    for (int s = 0; s < SV; ++s)
-      Elem<T>::unpack(*(const u32x4*)(src + row * p.ssn + vec * 16 + s * PV), x + s * PV);
-    u32x4 out;
-    unsigned w[4];
+    for (int u = 0; u < 4; ++u) {
+      const long long e = min(e0 + u * kQuantThreads, hi - 1);     // past the slice: a repeat, not stored
+      const long long row = e >> cshift;
+      const int vec = (int)e & cmask;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      w[i] = encode2(x[4 * i] / mult, x[4 * i + 1] / mult) | (encode2(x[4 * i + 2] / mult, x[4 * i + 3] / mult) << 16);
-    out.x = w[0]; out.y = w[1]; out.z = w[2]; out.w = w[3];
-    *(u32x4*)(dst + row * p.dsn + vec * 16) = out;
+      for (int s = 0; s < SV; ++s) raw[u][s] = *(const u32x4*)(src + row * p.ssn + vec * 16 + s * PV);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long e = e0 + u * kQuantThreads;
+      if (e >= hi) break;
+      float x[16];
+#pragma unroll
+      for (int s = 0; s < SV; ++s) Elem<T>::unpack(raw[u][s], x + s * PV);
+      unsigned w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        w[i] = encode2(x[4 * i] / mult, x[4 * i + 1] / mult) | (encode2(x[4 * i + 2] / mult, x[4 * i + 3] / mult) << 16);
+      u32x4 out;
+      out.x = w[0]; out.y = w[1]; out.z = w[2]; out.w = w[3];
+      *(u32x4*)(dst + (e >> cshift) * p.dsn + ((int)e & cmask) * 16) = out;
+    }
   }
 }
 

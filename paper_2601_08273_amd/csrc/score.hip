@@ -853,13 +853,16 @@ __global__ __launch_bounds__(kSaWaves * 64, 6) void sattn_pass1_with_emb(ScorePa
     return;
   }
   const int ncf = ((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw);   // crops per frame
-  const long long n_crops = (long long)ncf * p.F * p.B;
+  // (the host admits this launch only when its block count stays below 2^31: crop numbers fit 32 bits,
+  // and 32-bit divisions are all that stands in front of a riding block's first load)
+  const unsigned n_crops = (unsigned)ncf * (unsigned)p.F * (unsigned)p.B;
   const int half = threadIdx.x >> 8;
-  long long crop = 2ll * (blk - n_sattn) + half;
+  unsigned crop = 2u * (unsigned)(blk - n_sattn) + (unsigned)half;
   if (crop >= n_crops) crop = n_crops - 1;       // odd count: the idle half repeats the last crop
-  const int c = (int)(crop % ncf);
-  const long long fb = crop / ncf;
-  emb_mfma32_body<2>(p, sm.emb[half], threadIdx.x & 255, c, (int)(fb % p.F), (int)(fb / p.F));
+  const unsigned fb = crop / (unsigned)ncf;
+  const int c = (int)(crop - fb * (unsigned)ncf);
+  const unsigned bb = fb / (unsigned)p.F;
+  emb_mfma32_body<2>(p, sm.emb[half], threadIdx.x & 255, c, (int)(fb - bb * (unsigned)p.F), (int)bb);
 }
 
 // =================================================================================================
