@@ -187,11 +187,6 @@ __global__ __launch_bounds__(256) void attn_partial_valu(AttnParams p) {
 // =================================================================================================
 // MFMA partial kernel (bf16): helpers
 // =================================================================================================
-// r / G for a query-row number r < 4096 and a group size G <= 4096 without an integer division (which
-// costs some forty instructions in front of a block's transfers): (r + 1/2) * (1/G) lies at least
-// 1/(2G) away from every integer, hundreds of times the rounding error of the two operations.
-__device__ __forceinline__ int row_div_group(int r, float inv_g) { return (int)(((float)r + 0.5f) * inv_g); }
-
 constexpr int kMfmaTile = 32;         // tokens per tile the host-side split heuristic counts in
 constexpr float kRescaleGap = 8.f;    // log2 units, see the lazy rescale in the kernel
 

@@ -154,6 +154,12 @@ __device__ __forceinline__ int wave_reduce_i32(int v, Op op) {
 __device__ __forceinline__ float wave_max(float v) { return rows4_max(row16_max(v)); }
 __device__ __forceinline__ float wave_sum(float v) { return rows4_sum(row16_sum(v)); }
 
+// r / G for 0 <= r < 2^20 without the integer division sequence (some forty instructions):
+// (r + 1/2) * (1/G) lies at least 1/(2G) away from every integer, hundreds of times the rounding error
+// of the two operations (checked exhaustively for every r below 2^20 and every G up to 256, with the
+// reciprocal one unit in the last place off in either direction).
+__device__ __forceinline__ int row_div_group(int r, float inv_g) { return (int)(((float)r + 0.5f) * inv_g); }
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- HBM -> LDS transfers without registers in between -------------------------------------------
@@ -282,6 +288,10 @@ struct ScoreParams {
   float* s_spa;      // [B, Nv]
   int n_tile;        // token tiles of pass 1
   int n_rsplit;      // runs the query rows of a KV head are cut into (one block each)
+  // what every wave of the sweeps would otherwise divide out for itself (filled in by launch_score)
+  int rows_per_split;            // rows of a run: whole 64-row chunks
+  int q_step_i, q_step_g;        // 64 / G and 64 % G: how (i, g) of row r = i*G + g move from chunk to chunk
+  int q_last_i, q_last_g;        // (i, g) of the KV head's last row
 };
 hipError_t launch_score(const ScoreParams& p, hipStream_t st);
 int score_token_tile(int dtype);   // tokens per block in the s_attn passes
