@@ -163,19 +163,26 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
 
   const uint16_t* kbase = (const uint16_t*)p.k_layers[layer] + (long long)b * p.sb + (long long)hk * p.sh +
                           (long long)p.vis_off * p.sn;
-  // this wave's keys as A operands: token tb*16 + j, head-dim elements (ks*4 + g)*8 .. +8.  Which eight
-  // elements ride in which slot of a contraction step is free as long as keys and queries agree; with the
-  // four lane groups on adjacent pieces, one load instruction reads 64 contiguous bytes of each of its 16
-  // rows (16 cache lines) instead of four 16-byte pieces a quarter row apart (32 lines): the loads of a
-  // block's 256 keys, which nothing overlaps, go out in half the time.
-  bf16x8 kop[TBW][KS];
+  // This wave's keys as A operands: token tb*16 + j, head-dim elements (ks*4 + g)*8 .. +8 (which eight
+  // elements ride in which slot of a contraction step is free as long as keys and queries agree).
+  // An operand register wants 16 bytes of *its own* row in every lane; loaded that way, neighbouring
+  // lanes read rows a whole row stride apart and the address unit takes a clock per lane (64 per
+  // instruction: the 16 waves of a compute unit would queue there for 3.4 us with nothing to overlap).
+  // So the keys are loaded as they lie in memory -- lane l takes piece l % CPR of row l / CPR, a
+  // contiguous kilobyte per instruction -- and turned into operand layout through LDS: eight rows
+  // at a time through this wave's own 8-row strip of query buffer 0 (swizzled like the query chunks;
+  // the first query chunk lands in buffer 1 meanwhile), with no barrier, since a wave's LDS
+  // operations complete in order and nobody else touches its strip before the first chunk barrier.
+  constexpr int KRPI = 64 / CPR;                   // rows per load instruction
+  constexpr int KNI = TPW / KRPI;                  // load instructions per wave
+  constexpr int IPR = 8 / KRPI;                    // load instructions per 8-row round
+  static_assert(TPW % 8 == 0 && 8 % KRPI == 0 && NW * 8 <= SattnSmem<D, PASS>::RCH, "key strips live in query buffer 0");
+  u32x4 kraw[KNI];
 #pragma unroll
-  for (int tb = 0; tb < TBW; ++tb) {
-    int n = n0 + tb * 16 + j;
+  for (int i = 0; i < KNI; ++i) {
+    int n = n0 + i * KRPI + lane / CPR;
     n = n < p.Nv ? n : p.Nv - 1;                     // in bounds; masked below
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      kop[tb][ks] = *(const bf16x8*)(kbase + (long long)n * p.sn + (ks * 4 + g) * 8);
+    kraw[i] = *(const u32x4*)(kbase + (long long)n * p.sn + (lane % CPR) * 8);
   }
   bool tok_ok[TBW][4];
 #pragma unroll
@@ -244,8 +251,27 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
       if (r < Rs) lse_reg = p.row_lse[((long long)bz * p.Hkv + hk) * Rs + r];
     }
   };
-  if (row_begin < row_end) request_chunk(0, row_begin);     // (every request is waited for at the top of its chunk)
-  int buf = 0;
+  if (row_begin < row_end) request_chunk(1, row_begin);     // (every request is waited for at the top of its chunk)
+  int buf = 1;
+  bf16x8 kop[TBW][KS];
+  {
+    unsigned char* strip = Qs + __builtin_amdgcn_readfirstlane(wave) * (8 * ROWB);
+    const int wr_row = lane / CPR;                                  // row of the round this lane's piece belongs to (+ ii * KRPI)
+#pragma unroll
+    for (int r = 0; r < TPW / 8; ++r) {
+#pragma unroll
+      for (int ii = 0; ii < IPR; ++ii) {
+        const int row8 = ii * KRPI + wr_row;
+        *(u32x4*)(strip + row8 * ROWB + (((lane % CPR) ^ lds_row_swizzle<D>(row8)) * 16)) = kraw[r * IPR + ii];
+      }
+      const int tb = r / 2, half = r % 2;                            // rows 8 * half .. of 16-token block tb
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 v = *(const bf16x8*)(strip + (j & 7) * ROWB + (((ks * 4 + g) ^ lds_row_swizzle<D>(j & 7)) * 16));
+        if ((j >> 3) == half) kop[tb][ks] = v;
+      }
+    }
+  }
   for (int r0 = row_begin; r0 < row_end; r0 += RCH, buf ^= 1) {
     wait_vmcnt<0>();                          // this wave's share of the chunk (and its normalisers) has arrived
     if (PASS == 2 && tid < RCH) sm.lse_s[buf][tid] = lse_reg;
