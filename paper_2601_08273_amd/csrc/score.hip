@@ -1054,12 +1054,30 @@ int score_token_tile(int dtype) { return dtype == HIPPO_DTYPE_BF16 ? kSaMfmaTile
 
 // Row splits of the s_attn sweeps (bf16 path): enough blocks for two per compute unit, which is what
 // lets the MFMA and the exp work of different waves overlap; a split keeps at least two 64-row chunks.
+// How many runs the query rows of a KV head are cut into (one block of the sweeps per run).  A compute
+// unit holds two sweep blocks; measured at the 16K shape, two co-resident blocks take 2.1 us per 64-row
+// chunk each, a block alone 1.29 us, and a block's start (keys, first chunk) 3.2 resp. 2.5 us.  The
+// blocks are dealt to the compute units in rounds, so what counts is the busiest unit: ceil(blocks / 256)
+// blocks, two at a time, an odd last one alone.  520 unsplit blocks of 28 chunks, for example, put a third
+// block on a few units, which then start a 28-chunk sweep when all others are done (91 us against 81-83
+// with three or four runs); 256 blocks of 14 chunks are best cut in two (one round, two blocks per unit).
 int score_row_splits(int dtype, long long blocks_unsplit, int rows_per_kv_head) {
   if (dtype != HIPPO_DTYPE_BF16) return 1;
   const int chunks = (rows_per_kv_head + 63) / 64;
-  int rs = 1;
-  while (rs < 4 && blocks_unsplit * rs < 2 * kNumCU && chunks / (rs * 2) >= 2) rs *= 2;
-  return rs;
+  int best = 1;
+  double best_cost = 0.0;
+  for (int rs = 1; rs <= 4; ++rs) {
+    if (rs > 1 && chunks / rs < 2) break;                       // at least two chunks per block
+    const int cpb = (chunks + rs - 1) / rs;                     // chunks per block
+    const long long per_cu = (blocks_unsplit * rs + kNumCU - 1) / kNumCU;
+    const double pair = cpb * 2.1 + 3.2, alone = cpb * 1.29 + 2.5;
+    const double cost = (double)(per_cu / 2) * pair + (per_cu % 2 ? alone : 0.0);
+    if (rs == 1 || cost < best_cost * 0.97) {                   // a finer cut has to pay for its extra column partials
+      best = rs;
+      best_cost = cost;
+    }
+  }
+  return best;
 }
 
 template <typename T, int D>

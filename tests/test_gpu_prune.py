@@ -55,6 +55,8 @@ def test_score_on_configs(hippo, name):
     (2, 5, 8, 2, 128, 4, 12, 16, 0, 1, (6, 8)),    # 48-token crops tiling the grid exactly
     (1, 6, 4, 1, 128, 2, 14, 17, 5, 0, (6, 8)),    # 48-token crops cut by both edges (2-row and 1-column rests)
     (1, 4, 2, 1, 64, 3, 10, 14, 1, 1, (5, 7)),     # 35-token crops: barely past the two-block kernel
+    (1, 96, 16, 2, 64, 85, 16, 16, 5, 3, (5, 5)),  # 170 key tiles x 12 row chunks: the sweeps cut the rows in three runs
+    (1, 40, 14, 2, 64, 33, 16, 16, 0, 0, (5, 5)),  # 66 key tiles x 5 row chunks: two runs of 3 and 2 chunks
 ])
 def test_score_random_shapes(hippo, dtype, shape):
     B, L, H, Hkv, d, F, gh, gw, off, tail, (ch, cw) = shape
