@@ -75,7 +75,8 @@ int plan_attention(int call, const hippo_kv_desc* kv, int q_len, int n_total, in
     // one block per compute unit (measured at the 16K configuration: 48 or 80-128 slices per KV head
     // are all slower than 64), but never slices thinner than one 32-token tile
     const long long per_split = (long long)kv->batch * kv->n_kv_heads * pl->n_chunks;
-    S = (int)((kNumCU + per_split - 1) / per_split);
+    S = (int)(kNumCU / per_split);          // rounded down: a block beyond the last compute unit would share one
+    if (S < 1) S = 1;
     const int cap = n_tiles / min_tiles_per_block;
     if (S > cap) S = cap;
   }
