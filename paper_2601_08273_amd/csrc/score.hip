@@ -411,16 +411,30 @@ __global__ __launch_bounds__(256) void sattn_row_lse(ScoreParams p) {
   }
 }
 
+// Sum over layers, KV heads and row runs of the column partials of token jj of batch element b, in index
+// order, eight loads in flight at a time (a loop of one load and one add per turn would make every partial
+// its own trip to memory).
+__device__ __forceinline__ float sum_col_partials(const ScoreParams& p, int b, long long jj) {
+  const int nvh = p.Hkv * p.n_rsplit;
+  float a = 0.f;
+  for (int layer = 0; layer < p.n_layers; ++layer)
+    for (int hk0 = 0; hk0 < nvh; hk0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        v[q] = p.col_part[(((long long)layer * p.B + b) * nvh + min(hk0 + q, nvh - 1)) * p.Nv + jj];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) a += (hk0 + q < nvh) ? v[q] : 0.f;
+    }
+  return a;
+}
+
 // s_attn[b,j] = sum_hk col_part / (H L)  (+ running layer sum)
 __global__ __launch_bounds__(256) void sattn_finalize(ScoreParams p) {
   const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
   if (e >= (long long)p.B * p.Nv) return;
   const int b = (int)(e / p.Nv), jj = (int)(e % p.Nv);
-  float a = 0.f;
-  const int nvh = p.Hkv * p.n_rsplit;
-  for (int layer = 0; layer < p.n_layers; ++layer)
-    for (int hk = 0; hk < nvh; ++hk)
-      a += p.col_part[(((long long)layer * p.B + b) * nvh + hk) * p.Nv + jj];
+  float a = sum_col_partials(p, b, jj);
   a /= (float)p.H * (float)p.L;
   if (p.attn_mass_inout != nullptr) {
     a += p.attn_mass_inout[e];
@@ -922,11 +936,7 @@ __global__ __launch_bounds__(256) void fuse_scores(ScoreParams p) {
     for (int i = tid; i < p.P; i += 256) {
       const long long e = base + i;
       const int jj = f * p.P + i;
-      float a = 0.f;
-      const int nvh = p.Hkv * p.n_rsplit;
-      for (int layer = 0; layer < p.n_layers; ++layer)
-        for (int hk = 0; hk < nvh; ++hk)
-          a += p.col_part[(((long long)layer * p.B + b) * nvh + hk) * p.Nv + jj];
+      float a = sum_col_partials(p, b, jj);
       a /= (float)p.H * (float)p.L;
       if (p.attn_mass_inout != nullptr) {
         a += p.attn_mass_inout[e];
@@ -975,7 +985,6 @@ __global__ __launch_bounds__(256) void fuse_scores_reg(ScoreParams p) {
   __shared__ float red[3][4];
   const int f = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long base = (long long)b * p.Nv + (long long)f * p.P;
-  const int nvh = p.Hkv * p.n_rsplit;
   const bool on[3] = {(p.flags & HIPPO_SCORE_ATTN) != 0, (p.flags & HIPPO_SCORE_TEMP) != 0,
                       (p.flags & HIPPO_SCORE_SPA) != 0};
   float x[3][NPT];
@@ -984,11 +993,10 @@ __global__ __launch_bounds__(256) void fuse_scores_reg(ScoreParams p) {
     const int i = tid + 256 * u;
     const bool ok = i < p.P;
     x[0][u] = x[1][u] = x[2][u] = 0.f;
+    if (ok && on[1]) x[1][u] = p.s_temp[base + i];
+    if (ok && on[2]) x[2][u] = p.s_spa[base + i];
     if (ok && on[0]) {
-      float a = 0.f;
-      for (int layer = 0; layer < p.n_layers; ++layer)
-        for (int hk = 0; hk < nvh; ++hk)
-          a += p.col_part[(((long long)layer * p.B + b) * nvh + hk) * p.Nv + (long long)f * p.P + i];
+      float a = sum_col_partials(p, b, (long long)f * p.P + i);
       a /= (float)p.H * (float)p.L;
       if (p.attn_mass_inout != nullptr) {
         a += p.attn_mass_inout[base + i];
@@ -997,8 +1005,6 @@ __global__ __launch_bounds__(256) void fuse_scores_reg(ScoreParams p) {
       p.s_attn[base + i] = a;
       x[0][u] = a;
     }
-    if (ok && on[1]) x[1][u] = p.s_temp[base + i];
-    if (ok && on[2]) x[2][u] = p.s_spa[base + i];
   }
   auto reduce3 = [&](float (&v)[3]) {                  // block sums of three values at once
 #pragma unroll
