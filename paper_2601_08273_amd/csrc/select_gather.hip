@@ -145,9 +145,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
 #pragma unroll
     for (int c = 0; c < NC; ++c) keys[c] = (slot_index(c) < p.Nv) ? score_key(__uint_as_float(keys[c])) : 0u;
   }
-  auto key_at = [&](int c) -> unsigned {     // NC = 0: key of chunk c for this thread (index must be < Nv)
-    return score_key(sc[c * kSelThreads + tid]);
-  };
   // ---- radix select of the k-th largest key ----
   unsigned prefix = 0, need = (unsigned)p.k;   // `need` keys still wanted among those matching prefix
   const int shifts[3] = {20, 8, 0};
@@ -171,11 +168,17 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
         if ((keys[c] & masks[pass]) == prefix && (pass > 0 || keys[c] != 0u))
           atomicAdd(&h[hist_slot((keys[c] >> shifts[pass]) & dmask[pass])], 1u);
     } else {
-      for (int c = 0; c < n_chunks; ++c)
-        if (c * kSelThreads + tid < p.Nv) {
-          const unsigned key = key_at(c);
-          if ((key & masks[pass]) == prefix) atomicAdd(&h[hist_slot((key >> shifts[pass]) & dmask[pass])], 1u);
-        }
+      for (int c0 = 0; c0 < n_chunks; c0 += 8) {         // eight scores in flight per thread
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = sc[min((c0 + q) * kSelThreads + tid, p.Nv - 1)];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          if ((c0 + q) * kSelThreads + tid < p.Nv) {
+            const unsigned key = score_key(v[q]);
+            if ((key & masks[pass]) == prefix) atomicAdd(&h[hist_slot((key >> shifts[pass]) & dmask[pass])], 1u);
+          }
+      }
     }
     __syncthreads();
     if (pass == 2) {
@@ -235,14 +238,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
 
   // ---- compaction in index order ----
   __syncthreads();
-  auto flags = [&](int c, bool& gt, bool& eq) {        // NC = 0 path
-    gt = eq = false;
-    if (c * kSelThreads + tid < p.Nv) {
-      const unsigned key = key_at(c);
-      gt = key > thr;
-      eq = key == thr;
-    }
-  };
   if (CACHED) {
     // counts of keys above / equal to the threshold, packed (both fit 16 bits: a block caches at
     // most 40960 keys).  Index order inside a wave is (group of VW slots, lane, slot in the group):
@@ -279,9 +274,16 @@ __global__ __launch_bounds__(kSelThreads) void topk_select(SelectParams p) {
     if (tid == 0) { run_gt = 0; run_eq = 0; }
     __syncthreads();
     const unsigned long long below = (1ull << lane) - 1ull;
+    float ahead = sc[min(tid, p.Nv - 1)];                // the next chunk's score travels under this chunk's barriers
     for (int c = 0; c < n_chunks; ++c) {
-      bool gt, eq;
-      flags(c, gt, eq);
+      const float mine = ahead;
+      if (c + 1 < n_chunks) ahead = sc[min((c + 1) * kSelThreads + tid, p.Nv - 1)];
+      bool gt = false, eq = false;
+      if (c * kSelThreads + tid < p.Nv) {
+        const unsigned key = score_key(mine);
+        gt = key > thr;
+        eq = key == thr;
+      }
       const unsigned long long bg = __ballot(gt), be = __ballot(eq);
       const unsigned my_gt = __popcll(bg & below), my_eq = __popcll(be & below);
       if (lane == 0) { wg[wave] = __popcll(bg); we[wave] = __popcll(be); }
