@@ -292,6 +292,7 @@ struct ScoreParams {
   int rows_per_split;            // rows of a run: whole 64-row chunks
   int q_step_i, q_step_g;        // 64 / G and 64 % G: how (i, g) of row r = i*G + g move from chunk to chunk
   int q_last_i, q_last_g;        // (i, g) of the KV head's last row
+  int emb_run;                   // consecutive frames of one crop position that a block of the frame-run kernel owns
 };
 hipError_t launch_score(const ScoreParams& p, hipStream_t st);
 int score_token_tile(int dtype);   // tokens per block in the s_attn passes

@@ -880,20 +880,233 @@ __device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem&
   }
 }
 
+// =================================================================================================
+// s_temp and s_spa on MFMA, crops of at most 32 tokens, at most 512 channels: frame-run variant.
+// A block of eight waves owns ONE crop position over a run of consecutive frames, so a frame's crop
+// is fetched once and serves as "this frame" for its Gram matrix (Eq. 5-6; its diagonal holds the
+// norms) and as "the neighbour" of the frame before and after it (Eq. 3-4) -- against four fetches
+// per crop when every (crop, frame) is a block of its own.  Wave w owns channels 64w .. 64w+63 (two
+// MFMA channel steps) of all 32 rows; the eight partial Gram and dot blocks are summed through LDS.
+// The operands travel HBM -> LDS by direct transfers, a lane fetching 16 bytes of a 128-byte row
+// segment next to its neighbour's (an MFMA operand lane holds ITS OWN row, so fetching operands
+// straight into registers makes neighbouring lanes read rows far apart, and the address unit then
+// spends a clock per lane instead of a clock per four); the wave reads them back in operand layout
+// from its own 4 KB strip, whose rows are XOR-swizzled against bank conflicts.  The strip then
+// carries the wave's partial Gram blocks to the reduction, so the next frame's transfer is requested
+// once the reduction has read them and lands under the rest of the frame's arithmetic.
+// =================================================================================================
+struct EmbRunSmem {
+  static constexpr int MP = 32;
+  static constexpr int NW = 8;
+  __align__(16) unsigned char strip[NW][4096];      // operands in (32 rows x 128 B), then Gram partials out (3 x 64 x 16 B)
+  float redd[NW][2][16];                            // diagonals of the (this frame) x (frame before) blocks
+  float G[MP][MP + 1];
+  float dotv[MP];
+  int tok_s[MP];
+};
+
+// One crop position `pos` of batch element b over the frames f0 .. f0 + p.emb_run - 1 (cut at the
+// video's end), by the 512 threads of a block; every thread must call it (block-wide barriers).
+__device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem& sm, const int tid, const int pos,
+                                               const int f0, const int b) {
+  constexpr int MP = EmbRunSmem::MP;
+  constexpr int NW = EmbRunSmem::NW;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, g = lane >> 4;
+  const int ncx = (p.gw + p.cw - 1) / p.cw;
+  const int cy = pos / ncx, cx = pos % ncx;
+  const int y0 = cy * p.ch, x0 = cx * p.cw;
+  const int mh = min(p.ch, p.gh - y0), mw = min(p.cw, p.gw - x0);
+  const int M = mh * mw;
+  if (tid < MP) {
+    const int t = tid < M ? tid : M - 1;            // padding slots repeat the last token
+    sm.tok_s[tid] = (y0 + t / mw) * p.gw + x0 + t % mw;   // token within its frame
+  }
+  const int f_end = min(f0 + p.emb_run, p.F);       // the run: frames f0 .. f_end - 1
+  const int lo = max(f0 - 1, 0), hi = min(f_end, p.F - 1);   // frames fetched: the run and its neighbours
+  const int de = p.emb ? p.emb_dim : p.Hkv * p.D;
+  const bool keys_as_emb = p.emb == nullptr;
+  const int dsh = p.D == 128 ? 7 : 6;
+  __syncthreads();
+
+  // Transfer i of a frame (0..3) brings rows 8i .. 8i+7 of the crop: lane l fetches, for strip
+  // position l % 8 of row 8i + l / 8, the 16-byte piece (l % 8) ^ (row & 7) of the wave's 128 bytes.
+  // With keys as the embedding, channel c is element c % D of KV head c / D (D is a power of two).
+  const uint16_t* src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = i * 8 + (lane >> 3);
+    const int c = wave * 64 + (((lane & 7) ^ (r & 7)) * 8);
+    const int cs = c < de ? c : 0;                  // a valid address either way; zeroed when read
+    const long long tokn = (long long)lo * p.P + sm.tok_s[r];
+    if (keys_as_emb)
+      src[i] = (const uint16_t*)p.k_cache + (long long)b * p.sb + (p.vis_off + tokn) * p.sn +
+               (long long)(cs >> dsh) * p.sh + (cs & (p.D - 1));
+    else
+      src[i] = (const uint16_t*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok + cs;
+  }
+  const long long frame_step = (long long)p.P * (keys_as_emb ? p.sn : p.emb_stride_tok);
+  const bool wave_has_channels = wave * 64 < de;    // (uniform) waves beyond the last channel only keep the barriers
+  unsigned char* strip = &sm.strip[wave][0];
+  const unsigned strip_addr = (unsigned)(uintptr_t)strip;
+  auto request_frame = [&]() {
+    if (wave_has_channels) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        dma16(src[i], strip_addr + i * 1024);
+        src[i] += frame_step;
+      }
+    }
+  };
+  // operand (row block rbk, channel step u of the wave): lane (j, g) holds piece 4u + g of row 16 rbk + j
+  const bool wave_is_whole = wave * 64 + 64 <= de;  // (uniform) no channel of the wave's 64 lies beyond the last
+  auto operand = [&](int rbk, int u) -> bf16x8 {
+    const bf16x8 v = *(const bf16x8*)(strip + (rbk * 16 + j) * 128 + (((4 * u + g) ^ (j & 7)) * 16));
+    if (wave_is_whole) return v;
+    return wave * 64 + u * 32 + g * 8 < de ? v : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+  };
+  // 1 / sqrt(x) by the hardware's reciprocal square root (1 ulp), which ignores denormals: tiny
+  // arguments are scaled by 2^64 first, the result by 2^32; 0 for a zero-norm row.  (The riding
+  // blocks compete with the sweep for vector-instruction issue and nothing else, so what the crop's
+  // closing arithmetic costs in instructions is what the embedding terms cost the launch.)
+  auto inv_sqrt = [](float x) -> float {
+    const bool tiny = x < 0x1p-60f;
+    const float r = __builtin_amdgcn_rsqf(tiny ? x * 0x1p64f : x);
+    return x > 0.f ? (tiny ? r * 0x1p32f : r) : 0.f;
+  };
+  const float inv_M = 1.f / (float)M;
+
+  // state of the tokens' temporal term, kept by lane 0 of each 16-lane row (token a = tid / 16):
+  // 1 / norm of the last two frames, and their dot product
+  float inv_n1 = 0.f, inv_n2 = 0.f, dot1 = 0.f;
+  const int a = tid >> 4, c0 = (tid & 15) * 2;
+  const long long out_base = (long long)b * p.Nv + sm.tok_s[a];
+
+  bf16x8 prev[2][2];                                // the operands of the frame before
+#pragma unroll
+  for (int rbk = 0; rbk < 2; ++rbk)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) prev[rbk][u] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+  request_frame();
+  for (int fr = lo; fr <= hi; ++fr) {
+    f32x4 gram[3], dot[2];
+    bf16x8 cur[2][2];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) gram[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    dot[0] = dot[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    wait_vmcnt<0>();                                // the frame is in this wave's strip
+#pragma unroll
+    for (int rbk = 0; rbk < 2; ++rbk)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) cur[rbk][u] = operand(rbk, u);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      gram[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[0][u], cur[0][u], gram[0], 0, 0, 0);
+      gram[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[0][u], cur[1][u], gram[1], 0, 0, 0);
+      gram[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[1][u], cur[1][u], gram[2], 0, 0, 0);
+#pragma unroll
+      for (int rbk = 0; rbk < 2; ++rbk)
+        dot[rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[rbk][u], prev[rbk][u], dot[rbk], 0, 0, 0);
+    }
+#pragma unroll
+    for (int rbk = 0; rbk < 2; ++rbk)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) prev[rbk][u] = cur[rbk][u];
+    // D[i][j']: a lane holds column j' = j, rows i = 4g..4g+3.  The strip's operands are in registers
+    // (a wave's LDS operations complete in order), so it can take the Gram partials now; of a dot
+    // block only the diagonal (token with itself) is needed: lane (j, g = j/4), element j%4
+#pragma unroll
+    for (int i = 0; i < 3; ++i) *(f32x4*)(strip + (i * 64 + lane) * 16) = gram[i];
+    if ((j >> 2) == g) {
+#pragma unroll
+      for (int rbk = 0; rbk < 2; ++rbk) {
+        float d = dot[rbk][0];
+#pragma unroll
+        for (int e = 1; e < 4; ++e)
+          if ((j & 3) == e) d = dot[rbk][e];
+        sm.redd[wave][rbk][j] = d;
+      }
+    }
+    __syncthreads();
+    // sum the eight channel slices in a fixed order: waves 0..2 one Gram block each, wave 3 the diagonals
+    if (wave < 3) {
+      const int blk = wave;
+      f32x4 v = *(const f32x4*)(&sm.strip[0][0] + (blk * 64 + lane) * 16);
+#pragma unroll
+      for (int w = 1; w < NW; ++w) v += *(const f32x4*)(&sm.strip[w][0] + (blk * 64 + lane) * 16);
+      const int ra = blk == 2 ? 1 : 0, rbk = blk == 0 ? 0 : 1;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sm.G[ra * 16 + 4 * g + e][rbk * 16 + j] = v[e];
+        sm.G[rbk * 16 + j][ra * 16 + 4 * g + e] = v[e];
+      }
+    } else if (wave == 3 && lane < MP) {
+      float d = sm.redd[0][lane >> 4][lane & 15];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) d += sm.redd[w][lane >> 4][lane & 15];
+      sm.dotv[lane] = d;
+    }
+    __syncthreads();
+    if (fr < hi) request_frame();                   // the strips are free again: the next frame travels meanwhile
+
+    // cosines of token a against tokens c0, c0 + 1 (16 lanes cover the crop; padding rows hold
+    // finite values and are masked); Eq. 5-6: their variance
+    const float ia = inv_sqrt(sm.G[a][a]);
+    const float cs0 = c0 < M ? sm.G[a][c0] * (ia * inv_sqrt(sm.G[c0][c0])) : 0.f;
+    const float cs1 = c0 + 1 < M ? sm.G[a][c0 + 1] * (ia * inv_sqrt(sm.G[c0 + 1][c0 + 1])) : 0.f;
+    const float mu = row16_sum(cs0 + cs1) * inv_M;
+    const float d0 = c0 < M ? cs0 - mu : 0.f, d1 = c0 + 1 < M ? cs1 - mu : 0.f;
+    const float var = row16_sum(fmaf(d0, d0, d1 * d1)) * inv_M;
+    if ((tid & 15) == 0 && a < M) {
+      const float dcur = sm.dotv[a];                // <this frame, frame before>
+      if (fr >= f0 && fr < f_end) p.s_spa[out_base + (long long)fr * p.P] = var;
+      // Eq. 3-4 of the frame before, whose two neighbours are known now
+      if (fr > lo && fr - 1 >= f0) {
+        const float next = dcur * inv_n1 * ia, before = dot1 * inv_n1 * inv_n2;
+        p.s_temp[out_base + (long long)(fr - 1) * p.P] = 1.f - (fr - 1 > 0 ? 0.5f * (next + before) : next);
+      }
+      inv_n2 = inv_n1;
+      inv_n1 = ia;
+      dot1 = dcur;
+    }
+  }
+  // a run that reaches the video's last frame: that frame has no successor
+  if ((tid & 15) == 0 && a < M && hi < f_end)
+    p.s_temp[out_base + (long long)hi * p.P] = 1.f - (hi > 0 ? dot1 * inv_n1 * inv_n2 : 0.f);
+}
+
+// block number -> (crop position, run of frames, batch element), positions fastest
+__device__ __forceinline__ void emb_run32_block(const ScoreParams& p, EmbRunSmem& sm, const unsigned blk) {
+  const unsigned ncf = (unsigned)(((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw));   // crops per frame
+  const unsigned n_runs = (unsigned)((p.F + p.emb_run - 1) / p.emb_run);
+  const unsigned rest = blk / ncf, pos = blk - rest * ncf;
+  const unsigned bb = rest / n_runs, run = rest - bb * n_runs;
+  emb_run32_body(p, sm, threadIdx.x, (int)pos, (int)run * p.emb_run, (int)bb);
+}
+
+__global__ __launch_bounds__(512) void emb_scores_run32(ScoreParams p) {
+  __shared__ EmbRunSmem sm;
+  emb_run32_block(p, sm, blockIdx.x);
+}
+
 __global__ __launch_bounds__(256) void emb_scores_mfma32(ScoreParams p) {
   __shared__ Emb32Smem sm;
   emb_mfma32_body<4>(p, sm, threadIdx.x, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // Pass 1 of s_attn and the embedding terms in ONE launch: the first n_sattn blocks run the
-// (compute-bound) row-statistics sweep, two per compute unit; the remaining blocks run two crops
-// each and fill the third block slot of every compute unit, so the memory-bound embedding work
-// hides under the sweep instead of following it.  Three blocks fit a compute unit: 8 waves of at
-// most 80 registers each and the larger of the two shared-memory layouts (34 KB).
-template <int D>
+// (compute-bound) row-statistics sweep, two per compute unit; the remaining blocks run the crops and
+// fill the third block slot of the compute units, so the memory-bound embedding work hides under the
+// sweep instead of following it.  Three blocks fit a compute unit: 8 waves of at most 80 registers
+// each and the larger of the shared-memory layouts.  RUNS: a riding block owns one crop position over
+// a run of frames (up to 512 channels); otherwise it owns two crops, four waves each.
+template <int D, bool RUNS>
 __global__ __launch_bounds__(kSaWaves * 64, 6) void sattn_pass1_with_emb(ScoreParams p, int n_sattn) {
+  static_assert(kSaWaves == EmbRunSmem::NW, "the riding blocks use the sweep's block size");
   union Smem {
     SattnSmem<D, 1> sa;
+    EmbRunSmem run;
     Emb32Smem emb[2];
   };
   __shared__ Smem sm;
@@ -903,17 +1116,21 @@ __global__ __launch_bounds__(kSaWaves * 64, 6) void sattn_pass1_with_emb(ScorePa
     sattn_mfma_body<D, 1>(p, sm.sa, tile, rest % nvh, rest / nvh);
     return;
   }
-  const int ncf = ((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw);   // crops per frame
   // (the host admits this launch only when its block count stays below 2^31: crop numbers fit 32 bits,
   // and 32-bit divisions are all that stands in front of a riding block's first load)
-  const unsigned n_crops = (unsigned)ncf * (unsigned)p.F * (unsigned)p.B;
-  const int half = threadIdx.x >> 8;
-  unsigned crop = 2u * (unsigned)(blk - n_sattn) + (unsigned)half;
-  if (crop >= n_crops) crop = n_crops - 1;       // odd count: the idle half repeats the last crop
-  const unsigned fb = crop / (unsigned)ncf;
-  const int c = (int)(crop - fb * (unsigned)ncf);
-  const unsigned bb = fb / (unsigned)p.F;
-  emb_mfma32_body<2>(p, sm.emb[half], threadIdx.x & 255, c, (int)(fb - bb * (unsigned)p.F), (int)bb);
+  if constexpr (RUNS) {
+    emb_run32_block(p, sm.run, (unsigned)(blk - n_sattn));
+  } else {
+    const int ncf = ((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw);   // crops per frame
+    const unsigned n_crops = (unsigned)ncf * (unsigned)p.F * (unsigned)p.B;
+    const int half = threadIdx.x >> 8;
+    unsigned crop = 2u * (unsigned)(blk - n_sattn) + (unsigned)half;
+    if (crop >= n_crops) crop = n_crops - 1;       // odd count: the idle half repeats the last crop
+    const unsigned fb = crop / (unsigned)ncf;
+    const int c = (int)(crop - fb * (unsigned)ncf);
+    const unsigned bb = fb / (unsigned)p.F;
+    emb_mfma32_body<2>(p, sm.emb[half], threadIdx.x & 255, c, (int)(fb - bb * (unsigned)p.F), (int)bb);
+  }
 }
 
 // =================================================================================================
@@ -1096,14 +1313,17 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
   return hipGetLastError();
 }
 
+// riders: 0 = pass 1 in a launch of its own, else that many riding blocks (run_riders: of the frame-run kind)
 template <int D>
-static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st, bool with_emb) {
+static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st, long long riders, bool run_riders) {
   dim3 grid(p.n_tile, p.Hkv * p.n_rsplit, p.Bz);
-  if (with_emb) {
+  if (riders > 0) {
     const long long n_sattn = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.Bz;
-    const long long n_crops = (long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B;
-    hipLaunchKernelGGL((sattn_pass1_with_emb<D>), dim3((unsigned)(n_sattn + (n_crops + 1) / 2)),
-                       dim3(kSaWaves * 64), 0, st, p, (int)n_sattn);
+    const dim3 fused((unsigned)(n_sattn + riders));
+    if (run_riders)
+      hipLaunchKernelGGL((sattn_pass1_with_emb<D, true>), fused, dim3(kSaWaves * 64), 0, st, p, (int)n_sattn);
+    else
+      hipLaunchKernelGGL((sattn_pass1_with_emb<D, false>), fused, dim3(kSaWaves * 64), 0, st, p, (int)n_sattn);
   } else {
     hipLaunchKernelGGL((sattn_mfma<D, 1>), grid, dim3(kSaWaves * 64), 0, st, p);
   }
@@ -1127,13 +1347,26 @@ hipError_t launch_score(const ScoreParams& p_in, hipStream_t st) {
   const bool accumulate_only = (p.flags & HIPPO_SCORE_ACCUMULATE_ONLY) != 0;
   // bf16 with the paper's small crops: the embedding terms ride in the launch of s_attn's pass 1
   const bool want_emb = (p.flags & (HIPPO_SCORE_TEMP | HIPPO_SCORE_SPA)) != 0;
-  const long long fused_blocks = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.Bz +
-      ((long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw) * p.F * p.B + 1) / 2;
-  const bool emb_rides = want_emb && !accumulate_only && (p.flags & HIPPO_SCORE_ATTN) &&
-                         p.dtype == HIPPO_DTYPE_BF16 && p.ch * p.cw <= 32 && fused_blocks < (1ll << 31);
+  // bf16 crops of at most 32 tokens.  Up to 512 channels a block sweeps one crop position over a run
+  // of frames; the runs are as long as still leaves every compute unit a block (at most 8 frames: a
+  // run fetches its two neighbour frames on top of its own).  Wider embeddings: a block per two crops.
+  const long long crops_per_frame = (long long)((p.gh + p.ch - 1) / p.ch) * ((p.gw + p.cw - 1) / p.cw);
+  {
+    const long long per_cu = crops_per_frame * p.F * p.B / kNumCU;
+    p.emb_run = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(8, p.F), per_cu));
+  }
+  const bool small_crops = p.dtype == HIPPO_DTYPE_BF16 && p.ch * p.cw <= 32;
+  const bool emb_in_runs = small_crops && (p.emb ? p.emb_dim : p.Hkv * p.D) <= 512;
+  const long long n_riders = emb_in_runs ? crops_per_frame * ((p.F + p.emb_run - 1) / p.emb_run) * p.B
+                                         : (crops_per_frame * p.F * p.B + 1) / 2;
+  const long long fused_blocks = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.Bz + n_riders;
+  const bool emb_rides = want_emb && !accumulate_only && (p.flags & HIPPO_SCORE_ATTN) && small_crops &&
+                         fused_blocks < (1ll << 31);
+  const long long riders = emb_rides ? n_riders : 0;
   if ((p.flags & HIPPO_SCORE_ATTN) || accumulate_only) {
     if (p.dtype == HIPPO_DTYPE_BF16)
-      e = (p.D == 128) ? launch_sattn_mfma<128>(p, st, emb_rides) : launch_sattn_mfma<64>(p, st, emb_rides);
+      e = (p.D == 128) ? launch_sattn_mfma<128>(p, st, riders, emb_in_runs)
+                       : launch_sattn_mfma<64>(p, st, riders, emb_in_runs);
     else
       e = (p.D == 128) ? launch_sattn_valu<float, 128>(p, st) : launch_sattn_valu<float, 64>(p, st);
     if (e != hipSuccess) return e;
@@ -1148,7 +1381,9 @@ hipError_t launch_score(const ScoreParams& p_in, hipStream_t st) {
     dim3 grid(ncy * ncx, p.F, p.B);
     if (p.dtype == HIPPO_DTYPE_BF16) {
       const int crop = p.ch * p.cw;
-      if (crop <= 32) hipLaunchKernelGGL(emb_scores_mfma32, grid, dim3(256), 0, st, p);
+      if (emb_in_runs && n_riders < (1ll << 31))
+        hipLaunchKernelGGL(emb_scores_run32, dim3((unsigned)n_riders), dim3(512), 0, st, p);
+      else if (crop <= 32) hipLaunchKernelGGL(emb_scores_mfma32, grid, dim3(256), 0, st, p);
       else if (crop <= 48) hipLaunchKernelGGL(emb_scores_mfma<3>, grid, dim3(256), 0, st, p);
       else hipLaunchKernelGGL(emb_scores_mfma<4>, grid, dim3(256), 0, st, p);
     } else {
