@@ -895,6 +895,9 @@ __device__ __forceinline__ void emb_mfma32_body(const ScoreParams& p, Emb32Smem&
 // carries the wave's partial Gram blocks to the reduction, so the next frame's transfer is requested
 // once the reduction has read them and lands under the rest of the frame's arithmetic.
 // =================================================================================================
+// 16 bytes of zeros in device memory: what a transfer lane fetches for channels beyond the last
+__device__ __align__(16) const unsigned char g_zero_piece[16] = {0};
+
 struct EmbRunSmem {
   static constexpr int MP = 32;
   static constexpr int NW = 8;
@@ -902,6 +905,7 @@ struct EmbRunSmem {
   float redd[NW][2][16];                            // diagonals of the (this frame) x (frame before) blocks
   float G[MP][MP + 1];
   float dotv[MP];
+  float inv_norm[MP];
   int tok_s[MP];
 };
 
@@ -933,38 +937,34 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
   // Transfer i of a frame (0..3) brings rows 8i .. 8i+7 of the crop: lane l fetches, for strip
   // position l % 8 of row 8i + l / 8, the 16-byte piece (l % 8) ^ (row & 7) of the wave's 128 bytes.
   // With keys as the embedding, channel c is element c % D of KV head c / D (D is a power of two).
+  // Pieces beyond the last channel are fetched from 16 bytes of zeros (and stay there from frame to
+  // frame), so the operands need no masking.
   const uint16_t* src[4];
+  const int c = wave * 64 + (((lane & 7) ^ ((lane >> 3) & 7)) * 8);   // (row & 7 is the same in all four transfers)
+  const long long src_step = c >= de ? 0 : (long long)p.P * (keys_as_emb ? p.sn : p.emb_stride_tok);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int r = i * 8 + (lane >> 3);
-    const int c = wave * 64 + (((lane & 7) ^ (r & 7)) * 8);
-    const int cs = c < de ? c : 0;                  // a valid address either way; zeroed when read
-    const long long tokn = (long long)lo * p.P + sm.tok_s[r];
-    if (keys_as_emb)
+    const long long tokn = (long long)lo * p.P + sm.tok_s[i * 8 + (lane >> 3)];
+    if (c >= de)
+      src[i] = (const uint16_t*)g_zero_piece;
+    else if (keys_as_emb)
       src[i] = (const uint16_t*)p.k_cache + (long long)b * p.sb + (p.vis_off + tokn) * p.sn +
-               (long long)(cs >> dsh) * p.sh + (cs & (p.D - 1));
+               (long long)(c >> dsh) * p.sh + (c & (p.D - 1));
     else
-      src[i] = (const uint16_t*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok + cs;
+      src[i] = (const uint16_t*)p.emb + (long long)b * p.emb_stride_b + tokn * p.emb_stride_tok + c;
   }
-  const long long frame_step = (long long)p.P * (keys_as_emb ? p.sn : p.emb_stride_tok);
-  const bool wave_has_channels = wave * 64 < de;    // (uniform) waves beyond the last channel only keep the barriers
   unsigned char* strip = &sm.strip[wave][0];
   const unsigned strip_addr = (unsigned)(uintptr_t)strip;
   auto request_frame = [&]() {
-    if (wave_has_channels) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        dma16(src[i], strip_addr + i * 1024);
-        src[i] += frame_step;
-      }
+    for (int i = 0; i < 4; ++i) {
+      dma16(src[i], strip_addr + i * 1024);
+      src[i] += src_step;
     }
   };
   // operand (row block rbk, channel step u of the wave): lane (j, g) holds piece 4u + g of row 16 rbk + j
-  const bool wave_is_whole = wave * 64 + 64 <= de;  // (uniform) no channel of the wave's 64 lies beyond the last
   auto operand = [&](int rbk, int u) -> bf16x8 {
-    const bf16x8 v = *(const bf16x8*)(strip + (rbk * 16 + j) * 128 + (((4 * u + g) ^ (j & 7)) * 16));
-    if (wave_is_whole) return v;
-    return wave * 64 + u * 32 + g * 8 < de ? v : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+    return *(const bf16x8*)(strip + (rbk * 16 + j) * 128 + (((4 * u + g) ^ (j & 7)) * 16));
   };
   // 1 / sqrt(x) by the hardware's reciprocal square root (1 ulp), which ignores denormals: tiny
   // arguments are scaled by 2^64 first, the result by 2^32; 0 for a zero-norm row.  (The riding
@@ -990,34 +990,33 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
     for (int u = 0; u < 2; ++u) prev[rbk][u] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
   request_frame();
   for (int fr = lo; fr <= hi; ++fr) {
-    f32x4 gram[3], dot[2];
+    f32x4 dot[2];
     bf16x8 cur[2][2];
-#pragma unroll
-    for (int i = 0; i < 3; ++i) gram[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    dot[0] = dot[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
     wait_vmcnt<0>();                                // the frame is in this wave's strip
 #pragma unroll
     for (int rbk = 0; rbk < 2; ++rbk)
 #pragma unroll
       for (int u = 0; u < 2; ++u) cur[rbk][u] = operand(rbk, u);
+    // D[i][j']: a lane holds column j' = j, rows i = 4g..4g+3.  The strip's operands are in registers
+    // (a wave's LDS operations complete in order), so it can take the Gram partials at once
+    // (one block at a time: few accumulators live beside the two frames' operands)
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      gram[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[0][u], cur[0][u], gram[0], 0, 0, 0);
-      gram[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[0][u], cur[1][u], gram[1], 0, 0, 0);
-      gram[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[1][u], cur[1][u], gram[2], 0, 0, 0);
+    for (int i = 0; i < 3; ++i) {                    // Gram blocks (0,0) (0,1) (1,1)
+      f32x4 gram = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int rbk = 0; rbk < 2; ++rbk)
-        dot[rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[rbk][u], prev[rbk][u], dot[rbk], 0, 0, 0);
+      for (int u = 0; u < 2; ++u)
+        gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[i >> 1][u], cur[(i + 1) >> 1][u], gram, 0, 0, 0);
+      *(f32x4*)(strip + (i * 64 + lane) * 16) = gram;
     }
+    dot[0] = dot[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int rbk = 0; rbk < 2; ++rbk)
 #pragma unroll
-      for (int u = 0; u < 2; ++u) prev[rbk][u] = cur[rbk][u];
-    // D[i][j']: a lane holds column j' = j, rows i = 4g..4g+3.  The strip's operands are in registers
-    // (a wave's LDS operations complete in order), so it can take the Gram partials now; of a dot
-    // block only the diagonal (token with itself) is needed: lane (j, g = j/4), element j%4
-#pragma unroll
-    for (int i = 0; i < 3; ++i) *(f32x4*)(strip + (i * 64 + lane) * 16) = gram[i];
+      for (int u = 0; u < 2; ++u) {
+        dot[rbk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[rbk][u], prev[rbk][u], dot[rbk], 0, 0, 0);
+        prev[rbk][u] = cur[rbk][u];
+      }
+    // of a dot block only the diagonal (token with itself) is needed: lane (j, g = j/4), element j%4
     if ((j >> 2) == g) {
 #pragma unroll
       for (int rbk = 0; rbk < 2; ++rbk) {
@@ -1029,7 +1028,8 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
       }
     }
     __syncthreads();
-    // sum the eight channel slices in a fixed order: waves 0..2 one Gram block each, wave 3 the diagonals
+    // sum the eight channel slices in a fixed order: waves 0..2 one Gram block each (the diagonal
+    // blocks also give the rows' 1 / norm), wave 3 the diagonals of the dot blocks
     if (wave < 3) {
       const int blk = wave;
       f32x4 v = *(const f32x4*)(&sm.strip[0][0] + (blk * 64 + lane) * 16);
@@ -1040,6 +1040,13 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
       for (int e = 0; e < 4; ++e) {
         sm.G[ra * 16 + 4 * g + e][rbk * 16 + j] = v[e];
         sm.G[rbk * 16 + j][ra * 16 + 4 * g + e] = v[e];
+      }
+      if (blk != 1 && (j >> 2) == g) {              // D[j][j]: lane (j, g = j/4), element j%4
+        float d = v[0];
+#pragma unroll
+        for (int e = 1; e < 4; ++e)
+          if ((j & 3) == e) d = v[e];
+        sm.inv_norm[ra * 16 + j] = inv_sqrt(d);
       }
     } else if (wave == 3 && lane < MP) {
       float d = sm.redd[0][lane >> 4][lane & 15];
@@ -1052,9 +1059,9 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
 
     // cosines of token a against tokens c0, c0 + 1 (16 lanes cover the crop; padding rows hold
     // finite values and are masked); Eq. 5-6: their variance
-    const float ia = inv_sqrt(sm.G[a][a]);
-    const float cs0 = c0 < M ? sm.G[a][c0] * (ia * inv_sqrt(sm.G[c0][c0])) : 0.f;
-    const float cs1 = c0 + 1 < M ? sm.G[a][c0 + 1] * (ia * inv_sqrt(sm.G[c0 + 1][c0 + 1])) : 0.f;
+    const float ia = sm.inv_norm[a];
+    const float cs0 = c0 < M ? sm.G[a][c0] * (ia * sm.inv_norm[c0]) : 0.f;
+    const float cs1 = c0 + 1 < M ? sm.G[a][c0 + 1] * (ia * sm.inv_norm[c0 + 1]) : 0.f;
     const float mu = row16_sum(cs0 + cs1) * inv_M;
     const float d0 = c0 < M ? cs0 - mu : 0.f, d1 = c0 + 1 < M ? cs1 - mu : 0.f;
     const float var = row16_sum(fmaf(d0, d0, d1 * d1)) * inv_M;
