@@ -101,6 +101,32 @@ def test_score_explicit_embedding_and_flags(hippo, dtype):
         score_case(hippo, q, k, off, F, gh, gw, dtype, emb=emb, flags=flags, what="flags %d" % flags)
 
 
+@pytest.mark.parametrize("case", [
+    # B, F, gh, gw, crop, channels, flags: what the frame-run kernel of the embedding terms can be handed
+    (1, 130, 10, 10, (5, 5), 72, 6),     # 520 (crop, frame) pairs: runs of 2 frames; 72 channels: two waves, one ragged
+    (1, 87, 8, 12, (4, 4), 512, 6),      # 6 crops x 87 frames: runs of 2, the last run a single frame; all 512 channels
+    (2, 100, 10, 10, (5, 5), 136, 7),    # batch 2: runs of 3 frames, 100 = 33 x 3 + 1; riding in pass 1's launch
+    (1, 520, 6, 5, (5, 5), 64, 6),       # two crops per frame (one of them a single row): runs of 4 frames
+    (1, 9, 10, 10, (5, 5), 520, 6),      # 520 channels: beyond the frame-run kernel, a block per crop
+    (1, 9, 10, 10, (5, 5), 520, 7),      # ... and riding in pass 1's launch, two crops per block
+])
+def test_embedding_terms_over_runs_of_frames(hippo, case):
+    """Eq. 3-6 on bf16 embeddings with small crops: a block owns one crop position over a run of
+    consecutive frames; run lengths, a short last run, ragged channel counts and the boundary to
+    the wider-embedding kernels."""
+    B, F, gh, gw, (ch, cw), de, flags = case
+    r = np.random.default_rng(F + de)
+    nv = F * gh * gw
+    L, H, Hkv, d, off = 3, 2, 1, 64, 2
+    q = r.standard_normal((B, L, H, d))
+    k = r.standard_normal((B, Hkv, off + nv + 1, d))
+    emb = r.standard_normal((B, F, gh * gw, de))
+    emb[:, 1:] += 0.8 * emb[:, :-1]                  # neighbouring frames resemble each other
+    emb[:, 3 % F, 7] = 0.0                           # a zero-norm token: its cosines are defined as 0
+    score_case(hippo, q, k, off, F, gh, gw, "bf16", ch, cw, emb=emb.reshape(B, nv, de), flags=flags,
+               what="runs %s" % (case,))
+
+
 def test_score_layer_accumulation(hippo):
     """Outer layer sum of Eq. 2: two ACCUMULATE_ONLY-style calls; the last one fuses."""
     cfg = si.CONFIGS["tiny"]
