@@ -132,7 +132,8 @@ size_t hippo_workspace_bytes(int32_t call, const hippo_kv_desc* kv, const hippo_
  * scores_out [B, N_v] fp32 (required unless ACCUMULATE_ONLY).
  * components_out optional [3, B, N_v] fp32: raw s_attn (this call's, or accumulated), s_temp, s_spa.
  * Errors: NULL_ARG, BAD_SHAPE (l_txt < 1, N_v < 1, vis_offset + N_v > seq_len, crop too large,
- *         no term enabled), BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
+ *         no term enabled; beyond the launch limits: B * layers > 65535, more than 65535 frames,
+ *         bf16 with N_v > 65535 * 256 tokens), BAD_DTYPE, BAD_ALIGN, WORKSPACE_TOO_SMALL, HIP.
  */
 int hippo_score_tokens(const void* q_txt, int32_t l_txt,
                        const void* k_cache, const hippo_kv_desc* kv, int32_t seq_len,

@@ -183,8 +183,11 @@ int plan_score(const hippo_kv_desc* kv, const hippo_video_desc* vid, int l_txt, 
   const size_t row_lse = align_up(rows * sizeof(float), 256);
   pl->n_rsplit = score_row_splits(kv->dtype, (long long)pl->n_tile * kv->n_kv_heads * kv->batch * n_layers,
                                   l_txt * (kv->n_q_heads / kv->n_kv_heads));
-  // launch limits of the sweep (KV heads x row runs on grid y) and of the row merge (32 rows per block)
-  if ((long long)kv->n_kv_heads * pl->n_rsplit > 65535 || rows / 32 >= (1ull << 31)) return HIPPO_ERR_BAD_SHAPE;
+  // launch limits of the sweeps (key tiles on grid y, row runs x (layer, batch element) on grid z; the
+  // vector-ALU sweeps put KV heads on y) and of the row merge (32 rows per block)
+  if (pl->n_tile > 65535 || (long long)kv->batch * n_layers * pl->n_rsplit > 65535 || kv->n_kv_heads > 65535 ||
+      rows / 32 >= (1ull << 31))
+    return HIPPO_ERR_BAD_SHAPE;
   const size_t col = align_up((size_t)kv->batch * n_layers * kv->n_kv_heads * pl->n_rsplit * Nv * sizeof(float), 256);
   const size_t vec = align_up((size_t)kv->batch * Nv * sizeof(float), 256);
   size_t o = 0;

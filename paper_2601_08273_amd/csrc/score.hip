@@ -155,8 +155,7 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
   const int Rs = p.L * p.G;
   const float scale_log2 = rsqrtf((float)D) * kLog2e;
   // the query rows of a KV head are cut into n_rsplit runs of whole chunks; this block sweeps one
-  // the run index is the slow one: the blocks that sweep the other rows over the same 256 keys then lie
-  // n_tile * H_kv places apart in launch order -- on the same XCD, so the keys meet in its L2
+  // (vhk = KV head + H_kv * run)
   const int hk = vhk % p.Hkv, rs = vhk / p.Hkv;
   const int row_begin = rs * p.rows_per_split;
   const int row_end = min(Rs, row_begin + p.rows_per_split);
@@ -362,10 +361,17 @@ __device__ __forceinline__ void sattn_mfma_body(const ScoreParams& p, SattnSmem<
   }
 }
 
+// Launch order of the sweeps' blocks: KV head fastest, then key tile, then row run, then (layer,
+// batch element).  Consecutive blocks go to consecutive XCDs, so with 1, 2, 4 or 8 KV heads an XCD
+// sees the blocks of one or few heads only and its L2 fetches those heads' query rows instead of all
+// of them (every block re-reads the query rows of its head and run); the blocks that sweep the other
+// row run over the same 256 keys lie H_kv * n_tile places on -- on the same XCD, where the keys are.
+// Grid (H_kv, n_tile, n_rsplit * Bz).
 template <int D, int PASS>
 __global__ __launch_bounds__(kSaWaves * 64) void sattn_mfma(ScoreParams p) {
   __shared__ SattnSmem<D, PASS> sm;
-  sattn_mfma_body<D, PASS>(p, sm, blockIdx.x, blockIdx.y, blockIdx.z);
+  const int rs = blockIdx.z % p.n_rsplit;
+  sattn_mfma_body<D, PASS>(p, sm, blockIdx.y, blockIdx.x + p.Hkv * rs, blockIdx.z / p.n_rsplit);
 }
 
 // merge the per-tile row statistics: lse2 = m* + log2(sum_t l_t 2^(m_t - m*)).  A block takes 32
@@ -1118,9 +1124,10 @@ __global__ __launch_bounds__(kSaWaves * 64, 6) void sattn_pass1_with_emb(ScorePa
   };
   __shared__ Smem sm;
   const int blk = blockIdx.x;
-  if (blk < n_sattn) {
-    const int tile = blk % p.n_tile, rest = blk / p.n_tile, nvh = p.Hkv * p.n_rsplit;
-    sattn_mfma_body<D, 1>(p, sm.sa, tile, rest % nvh, rest / nvh);
+  if (blk < n_sattn) {                       // the order of sattn_mfma's grid: KV head fastest, then key tile, ...
+    const int hk = blk % p.Hkv, rest = blk / p.Hkv;
+    const int tile = rest % p.n_tile, rest2 = rest / p.n_tile;
+    sattn_mfma_body<D, 1>(p, sm.sa, tile, hk + p.Hkv * (rest2 % p.n_rsplit), rest2 / p.n_rsplit);
     return;
   }
   // (the host admits this launch only when its block count stays below 2^31: crop numbers fit 32 bits,
@@ -1323,7 +1330,8 @@ static hipError_t launch_sattn_valu(const ScoreParams& p, hipStream_t st) {
 // riders: 0 = pass 1 in a launch of its own, else that many riding blocks (run_riders: of the frame-run kind)
 template <int D>
 static hipError_t launch_sattn_mfma(const ScoreParams& p, hipStream_t st, long long riders, bool run_riders) {
-  dim3 grid(p.n_tile, p.Hkv * p.n_rsplit, p.Bz);
+  if (p.n_tile > 65535 || (long long)p.n_rsplit * p.Bz > 65535) return hipErrorInvalidValue;
+  dim3 grid(p.Hkv, p.n_tile, p.n_rsplit * p.Bz);
   if (riders > 0) {
     const long long n_sattn = (long long)p.n_tile * p.Hkv * p.n_rsplit * p.Bz;
     const dim3 fused((unsigned)(n_sattn + riders));
