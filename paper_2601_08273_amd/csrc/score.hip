@@ -1005,9 +1005,12 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
       for (int u = 0; u < 2; ++u) cur[rbk][u] = operand(rbk, u);
     // D[i][j']: a lane holds column j' = j, rows i = 4g..4g+3.  The strip's operands are in registers
     // (a wave's LDS operations complete in order), so it can take the Gram partials at once
-    // (one block at a time: few accumulators live beside the two frames' operands)
+    // (one block at a time: few accumulators live beside the two frames' operands).  A neighbour frame
+    // beyond the run is here for its norms and dot products: the diagonal blocks suffice.
+    const bool own_frame = fr >= f0 && fr < f_end;  // (uniform)
 #pragma unroll
     for (int i = 0; i < 3; ++i) {                    // Gram blocks (0,0) (0,1) (1,1)
+      if (i == 1 && !own_frame) continue;
       f32x4 gram = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int u = 0; u < 2; ++u)
@@ -1036,7 +1039,7 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
     __syncthreads();
     // sum the eight channel slices in a fixed order: waves 0..2 one Gram block each (the diagonal
     // blocks also give the rows' 1 / norm), wave 3 the diagonals of the dot blocks
-    if (wave < 3) {
+    if (wave < 3 && (own_frame || wave != 1)) {
       const int blk = wave;
       f32x4 v = *(const f32x4*)(&sm.strip[0][0] + (blk * 64 + lane) * 16);
 #pragma unroll
@@ -1064,16 +1067,19 @@ __device__ __forceinline__ void emb_run32_body(const ScoreParams& p, EmbRunSmem&
     if (fr < hi) request_frame();                   // the strips are free again: the next frame travels meanwhile
 
     // cosines of token a against tokens c0, c0 + 1 (16 lanes cover the crop; padding rows hold
-    // finite values and are masked); Eq. 5-6: their variance
+    // finite values and are masked); Eq. 5-6: their variance -- for the run's own frames only
     const float ia = sm.inv_norm[a];
-    const float cs0 = c0 < M ? sm.G[a][c0] * (ia * sm.inv_norm[c0]) : 0.f;
-    const float cs1 = c0 + 1 < M ? sm.G[a][c0 + 1] * (ia * sm.inv_norm[c0 + 1]) : 0.f;
-    const float mu = row16_sum(cs0 + cs1) * inv_M;
-    const float d0 = c0 < M ? cs0 - mu : 0.f, d1 = c0 + 1 < M ? cs1 - mu : 0.f;
-    const float var = row16_sum(fmaf(d0, d0, d1 * d1)) * inv_M;
+    float var = 0.f;
+    if (own_frame) {
+      const float cs0 = c0 < M ? sm.G[a][c0] * (ia * sm.inv_norm[c0]) : 0.f;
+      const float cs1 = c0 + 1 < M ? sm.G[a][c0 + 1] * (ia * sm.inv_norm[c0 + 1]) : 0.f;
+      const float mu = row16_sum(cs0 + cs1) * inv_M;
+      const float d0 = c0 < M ? cs0 - mu : 0.f, d1 = c0 + 1 < M ? cs1 - mu : 0.f;
+      var = row16_sum(fmaf(d0, d0, d1 * d1)) * inv_M;
+    }
     if ((tid & 15) == 0 && a < M) {
       const float dcur = sm.dotv[a];                // <this frame, frame before>
-      if (fr >= f0 && fr < f_end) p.s_spa[out_base + (long long)fr * p.P] = var;
+      if (own_frame) p.s_spa[out_base + (long long)fr * p.P] = var;
       // Eq. 3-4 of the frame before, whose two neighbours are known now
       if (fr > lo && fr - 1 >= f0) {
         const float next = dcur * inv_n1 * ia, before = dot1 * inv_n1 * inv_n2;
