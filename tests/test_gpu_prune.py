@@ -10,12 +10,16 @@ from parity_util import assert_close, assert_fused_close, assert_indices_consist
 pytestmark = pytest.mark.gpu
 
 
-def score_case(hippo, q_txt, k, vis_off, F, gh, gw, dtype, ch=5, cw=5, emb=None, flags=7, what=""):
+def score_case(hippo, q_txt, k, vis_off, F, gh, gw, dtype, ch=5, cw=5, emb=None, flags=7, what="", emb_pad=0):
     q_txt, k = prep(q_txt, dtype), prep(k, dtype)
     emb_h = None if emb is None else prep(emb, dtype)
     vid = hippo.video_desc(F, gh, gw, vis_off, ch, cw)
-    scores, comps = hippo.hippo_score_tokens(dev(q_txt, dtype), dev(k, dtype), vid,
-                                             emb=None if emb is None else dev(emb_h, dtype), flags=flags,
+    emb_d = None if emb is None else dev(emb_h, dtype)
+    if emb_pad:                                    # the same values as a view into rows emb_pad channels wider
+        wide = torch.zeros(emb_d.shape[:2] + (emb_d.shape[2] + emb_pad,), dtype=emb_d.dtype, device="cuda")
+        wide[..., :emb_d.shape[2]] = emb_d
+        emb_d = wide[..., :emb_d.shape[2]]
+    scores, comps = hippo.hippo_score_tokens(dev(q_txt, dtype), dev(k, dtype), vid, emb=emb_d, flags=flags,
                                              want_components=True)
     torch.cuda.synchronize()
     rs, rc = oracle.score_tokens(q_txt, k, vis_off, F, gh, gw, ch, cw, emb=emb_h, flags=flags)
@@ -124,7 +128,7 @@ def test_embedding_terms_over_runs_of_frames(hippo, case):
     emb[:, 1:] += 0.8 * emb[:, :-1]                  # neighbouring frames resemble each other
     emb[:, 3 % F, 7] = 0.0                           # a zero-norm token: its cosines are defined as 0
     score_case(hippo, q, k, off, F, gh, gw, "bf16", ch, cw, emb=emb.reshape(B, nv, de), flags=flags,
-               what="runs %s" % (case,))
+               what="runs %s" % (case,), emb_pad=24 if de == 136 else 0)   # one case with a token stride > channels
 
 
 def test_score_layer_accumulation(hippo):
