@@ -148,6 +148,9 @@ def test_score_argument_errors(lib):
     # shapes no kernel grid can hold are refused before the first launch: frames are a y dimension
     assert _score(lib, kv, h.video_desc(65536, 2, 2, 128), seq_len=1 << 20) == h.ERR_BAD_SHAPE
     assert _score(lib, kv, h.video_desc(65535, 2, 2, 128), seq_len=1 << 20, ws_bytes=4096) == h.ERR_WORKSPACE_TOO_SMALL
+    # ... and the key tiles of the bf16 sweeps (256 tokens each): 65535 of them at most
+    assert _score(lib, kv, h.video_desc(65535, 16, 17, 128), seq_len=1 << 25) == h.ERR_BAD_SHAPE
+    assert _score(lib, kv, h.video_desc(65535, 16, 16, 0), seq_len=65535 * 256, ws_bytes=4096) == h.ERR_WORKSPACE_TOO_SMALL
 
 
 def test_select_argument_errors(lib):
