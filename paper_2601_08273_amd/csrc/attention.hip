@@ -396,6 +396,18 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   // complete in issue order, so the wait for super-tile 0 below also covers the query block. ----
   const bool issuer = wave < ISSUERS;
   int issued = n_super < NST ? n_super : NST;              // super-tiles requested so far
+  // Appended rows: the block that copies them into the cache fetches them now, ahead of every transfer
+  // (loads return in order, so the transfer counts waited for below are not disturbed), and stores them
+  // after its slice: the copy's trip to memory hides behind the stream instead of following it.
+  const bool appends = APPEND && split == 0 && chunk == 0;
+  constexpr int APR = D / 8;                               // 16-byte pieces per bf16 row
+  const bool append_early = appends && p.q_len * APR <= WAVES * 64;
+  u32x4 app_k = {0u, 0u, 0u, 0u}, app_v = {0u, 0u, 0u, 0u};
+  if (APPEND && append_early && (int)threadIdx.x < p.q_len * APR) {
+    const long long src = (((long long)b * p.q_len + threadIdx.x / APR) * p.Hkv + hk) * D + (threadIdx.x % APR) * 8;
+    app_k = *(const u32x4*)((const uint16_t*)p.k_new + src);
+    app_v = *(const u32x4*)((const uint16_t*)p.v_new + src);
+  }
   if (issuer && issued > 0) issue_super(0);
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
@@ -637,7 +649,18 @@ __global__ __launch_bounds__(RB * TG * 64) void attn_partial_grid(AttnParams p) 
   else if (tg == 1) finish(std::integral_constant<int, 1>());
   else if (tg == 2) finish(std::integral_constant<int, 2 % TG>());
   else finish(std::integral_constant<int, 3 % TG>());
-  if (APPEND && split == 0 && chunk == 0) append_new_rows<uint16_t, D>(p, b, hk);
+  if (APPEND && appends) {
+    if (append_early) {
+      if ((int)threadIdx.x < p.q_len * APR) {
+        const long long dst = (long long)b * p.sb + (long long)hk * p.sh +
+                              (long long)(p.ctx_len + threadIdx.x / APR) * p.sn + (threadIdx.x % APR) * 8;
+        *(u32x4*)((uint16_t*)p.k_w + dst) = app_k;
+        *(u32x4*)((uint16_t*)p.v_w + dst) = app_v;
+      }
+    } else {
+      append_new_rows<uint16_t, D>(p, b, hk);
+    }
+  }
 }
 
 // =================================================================================================
